@@ -1,0 +1,199 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-attention hot path on one MI355X.
+
+One "step" = one xattn_decode call (partition + split-KV decode kernel + merge kernel) over one batch
+of synthetic input that is already resident in HBM.  Prints ONE JSON line:
+
+  metric/value/unit   KV-read GB/s of the whole call: sum_b kv_len[b] * n_kv_heads * 128 * 2 (K and V)
+                      * 2 B, divided by the time of one step (K steps back to back on one stream)
+  token_steps_per_s   batch * q_len / time of one step
+  roofline            the split-KV decode kernel alone against the 8 TB/s HBM peak; its duration is
+                      measured in a second pass with HIP events around each kernel
+  cpu_baseline        the fp64 CPU oracle, as it stands, timed on this machine's host cores
+  workloads           the same figures for the other large synthetic workloads
+  parity              GPU result against the oracle on the benchmarked inputs (all or sampled rows)
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0
+# HBM bytes per decode-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script (summaries under profiles/), scaled by the factor a plain copy kernel of known size gives.
+# None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def run_workload(w, steps, warmup, check_rows, cpu_baseline):
+    import numpy as np
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from workloads import bf16_to_f32
+
+    t0 = time.time()
+    lens = w.kv_lens()
+    q = w.make_q()
+    ks, vs = w.make_kv(lens)
+    kv_bytes = w.kv_bytes(lens)
+    log("[%s] generated %.2f GB of K/V for %d sequences in %.1f s" % (w.name, kv_bytes / 1e9, w.batch, time.time() - t0))
+    B, T, Hq, Hkv, D = w.batch, w.q_len, w.n_q_heads, w.n_kv_heads, w.head_dim
+    res = {"workload": w.name, "batch": B, "q_len": T, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D,
+           "kv_tokens": int(lens.sum()), "kv_bytes": kv_bytes, "kv_placement":
+           "xtensor: per-sequence virtual ranges, 2 MiB chunks in seeded random order" if w.xtensor else "plain allocations"}
+
+    t0 = time.time()
+    store = xa.KVStore(ks, vs, device=0, xtensor=w.xtensor, seed=w.seed)
+    log("[%s] placed K/V in %.1f s (%d chunks)" % (w.name, time.time() - t0, store.n_chunks))
+    try:
+        qd = torch.from_numpy(np.ascontiguousarray(q).view(np.int16)).cuda()
+        lens_d = torch.from_numpy(lens).cuda()
+        out = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((B, T, Hq), dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def step():
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, w.scale, out, lse, stream)
+
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 0)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t_wall = time.perf_counter()
+        e0.record(stream)
+        for _ in range(steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        t_wall = time.perf_counter() - t_wall
+        ms_step = e0.elapsed_time(e1) / steps
+        res["ms_per_step"] = ms_step
+        res["ms_per_step_wall"] = t_wall * 1e3 / steps
+        res["kv_read_GBps"] = kv_bytes / (ms_step * 1e-3) / 1e9
+        res["pct_of_hbm_peak"] = 100.0 * res["kv_read_GBps"] / HBM_PEAK_GBS
+        res["token_steps_per_s"] = B * T / (ms_step * 1e-3)
+
+        # second pass: per-kernel durations from events recorded inside the library, on the same stream
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 1)
+        xa.xattn_timing_read()
+        n_timed = min(steps, 2000)
+        for _ in range(n_timed):
+            step()
+        torch.cuda.synchronize()
+        n, dec_ms, mrg_ms = xa.xattn_timing_read()
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 0)
+        dec_ms_avg, mrg_ms_avg = dec_ms / max(n, 1), mrg_ms / max(n, 1)
+        achieved = kv_bytes / (dec_ms_avg * 1e-3) / 1e9
+        res["roofline"] = {"kernel": "split_decode_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(w.name),
+                           "algorithmic_bytes_per_launch": kv_bytes, "kernel_ms": dec_ms_avg,
+                           "merge_kernel_ms": mrg_ms_avg, "timed_launches": n}
+
+        # parity on the benchmarked inputs
+        import oracle
+        from gpu_util import errors
+        torch.cuda.synchronize()
+        out_h = out.cpu().numpy().view(np.uint16)
+        lse_h = lse.cpu().numpy()
+        sel = list(range(B)) if check_rows is None or check_rows >= B else \
+            sorted(set(np.linspace(0, B - 1, check_rows).astype(int).tolist() + [int(np.argmax(lens)), int(np.argmin(lens))]))
+        t0 = time.time()
+        ref_out, ref_lse = oracle.attn(q[sel], [ks[b] for b in sel], [vs[b] for b in sel], lens[sel], w.scale)
+        t_or = time.time() - t0
+        max_abs, rel_rows, rel_all, lse_err = errors(out_h[sel], lse_h[sel], ref_out, ref_lse)
+        res["parity"] = {"sequences_checked": len(sel), "max_abs": max_abs, "max_row_rel_l2": rel_rows,
+                         "rel_l2": rel_all, "lse_max_abs": lse_err,
+                         "pass": bool(max_abs <= 1e-2 and rel_rows <= 5e-3 and lse_err <= 1e-3)}
+        log("[%s] %.1f us/step  %.0f GB/s (%.1f%% of peak)  kernel %.1f us -> %.0f GB/s  merge %.1f us  parity %s"
+            % (w.name, ms_step * 1e3, res["kv_read_GBps"], res["pct_of_hbm_peak"], dec_ms_avg * 1e3, achieved,
+               mrg_ms_avg * 1e3, res["parity"]))
+
+        if cpu_baseline:
+            # The oracle as it stands on the host cores, over the sequences just checked.
+            sel_tokens = int(lens[sel].sum())
+            reps = max(1, min(5, int(10.0 / max(t_or, 1e-3))))
+            t0 = time.time()
+            for _ in range(reps):
+                oracle.attn(q[sel], [ks[b] for b in sel], [vs[b] for b in sel], lens[sel], w.scale)
+            t_cpu = (time.time() - t0) / reps
+            sel_bytes = sel_tokens * Hkv * D * 4
+            res["cpu_baseline"] = {"value": sel_bytes / t_cpu / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
+                                   "kind": "oracle",
+                                   "sample": "%d of %d sequences (%d KV tokens), %d repetitions, %.2f s each"
+                                             % (len(sel), B, sel_tokens, reps, t_cpu),
+                                   "token_steps_per_s": len(sel) * T / t_cpu}
+    finally:
+        store.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="qwen3_8b_decode")
+    ap.add_argument("--only", action="store_true", help="measure only --workload, not the other large workloads")
+    ap.add_argument("--check-sequences", type=int, default=None, help="sequences verified against the oracle (default all)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import workloads
+    from paper_2510_14686_amd import build as xbuild
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    if not os.path.exists(xbuild.LIB_PATH):
+        xbuild.build()
+
+    head = workloads.CONFIGS[args.workload]
+    main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True)
+    others = {}
+    if not args.only:
+        for name in workloads.CONFIG_ORDER:
+            if name in ("tiny", args.workload):
+                continue
+            r = run_workload(workloads.CONFIGS[name], args.steps, args.warmup, 24, cpu_baseline=False)
+            others[name] = {k: r[k] for k in ("ms_per_step", "kv_read_GBps", "pct_of_hbm_peak", "token_steps_per_s",
+                                              "kv_bytes", "kv_tokens", "batch", "q_len", "kv_placement", "parity")}
+            others[name]["roofline"] = r["roofline"]
+
+    line = {
+        "metric": "KV-read HBM GB/s (% of 8 TB/s) + attention token-steps/s, 1 MI355X",
+        "value": main_res["kv_read_GBps"], "unit": "GB/s",
+        "pct_of_hbm_peak": main_res["pct_of_hbm_peak"], "token_steps_per_s": main_res["token_steps_per_s"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic (seeded N(0,1) bf16, seeded lengths)",
+        "config": {"workload": main_res["workload"], "batch": main_res["batch"], "q_len": main_res["q_len"],
+                   "n_q_heads": main_res["n_q_heads"], "n_kv_heads": main_res["n_kv_heads"],
+                   "head_dim": main_res["head_dim"], "kv_tokens": main_res["kv_tokens"],
+                   "kv_bytes": main_res["kv_bytes"], "kv_placement": main_res["kv_placement"]},
+        "roofline": main_res["roofline"], "cpu_baseline": main_res.get("cpu_baseline"),
+        "parity": main_res["parity"], "workloads": others,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,162 @@
+/*
+ * xattn -- decode attention over xTensor-style KV memory on one AMD MI355X (gfx950).
+ *
+ * C ABI of libxattn.so.  Plain pointers and sizes only; every pointer says whether it is a HOST
+ * or a DEVICE pointer.  No exception crosses this boundary: every call returns an xattn_status
+ * (0 = success, negative = failure) and leaves a message for xattn_last_error().
+ *
+ * Paper: "xLLM Technical Report" (arXiv 2510.14686).  Passages cited below:
+ *   section 4.3   "Efficient Memory Management" (xTensor): a request's KV cache is contiguous in a
+ *                 reserved virtual range and is backed on demand by discrete fixed-size physical
+ *                 pages; operators receive the starting virtual address and offsets, no block table
+ *                 (paragraphs "Physical Memory Page Management ...", "On-demand Memory Mapping",
+ *                 "Operator Adaptation", and the address -> (page, offset) equation).
+ *   section 4.4.1 "MLA Optimization": the m+1 query tokens of a speculative step are multiplied with
+ *                 the same K, which is loaded once for all of them and Q stays resident.
+ *   section 4.4.3 "Layer 3: Fine-Grained Kernel-Level Optimization": work is balanced across compute
+ *                 units by token count and long sequences are split; "Layer 2": partial attention
+ *                 results are combined by an aggregation operator.
+ *   section 4.2   "Integrating Custom Operators": runtime shapes reach the kernels as arguments, so
+ *                 nothing on the host depends on their values (no host read of kv_lens, no sync).
+ */
+#ifndef XATTN_H_
+#define XATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XATTN_OK = 0,
+    XATTN_EINVAL = -1,       /* null pointer, non-positive size, inconsistent arguments */
+    XATTN_EUNSUPPORTED = -2, /* a valid request outside the supported set (see xattn_decode) */
+    XATTN_ENOMEM = -3,       /* device or virtual-address space exhausted */
+    XATTN_EHIP = -4          /* a HIP runtime call failed; the message names it */
+} xattn_status;
+
+/* Message of the calling thread's last failed call. HOST string, never NULL, valid until that
+ * thread's next failing call. */
+const char* xattn_last_error(void);
+
+/*
+ * Batched grouped-query decode attention (section 4.3 "Operator Adaptation", section 4.4.1).
+ *
+ * For sequence b, new query token t in [0, q_len) and query head h (KV head g = h / (n_q_heads /
+ * n_kv_heads)), with Lv = kv_lens[b] - q_len + t + 1 visible keys (the cached prefix plus new tokens
+ * 0..t: a causal mask inside the block of new tokens):
+ *     s_j = scale * <Q[b,t,h,:], K_b[j,g,:]>,  j in [0, Lv)
+ *     out[b,t,h,:] = sum_j softmax(s)_j * V_b[j,g,:]        lse[b,t,h] = ln sum_j exp(s_j)
+ * The key range is partitioned over the GPU's compute units by token count (sequences are split and
+ * short ones share a workgroup, section 4.4.3 Layer 3) and partial results are combined exactly by
+ * a log-sum-exp merge; accumulation is fp32, results are rounded to bf16 (nearest even).
+ *
+ * q        DEVICE  bf16 [batch, q_len, n_q_heads, head_dim], contiguous
+ * k_ptrs   DEVICE  array[batch] of DEVICE pointers; k_ptrs[b] -> bf16 [>= kv_lens[b], n_kv_heads,
+ *                  head_dim], row-major, 16-byte aligned.  Any device-accessible address works: an
+ *                  xtensor_map range or an ordinary allocation.  Rows past kv_lens[b] are never read.
+ * v_ptrs   DEVICE  same layout as K
+ * kv_lens  DEVICE  int32[batch]; keys visible to the LAST new token, i.e. prefix + q_len (the new
+ *                  tokens' K/V are already written).  Read on the device only.  A value < q_len
+ *                  leaves the tokens without visible keys with out = 0 and lse = -inf.
+ * batch    1..4096;  q_len 1..16;  head_dim must be 128;  n_q_heads a multiple of n_kv_heads;
+ *          (n_q_heads / n_kv_heads) * q_len <= 64.  Otherwise XATTN_EUNSUPPORTED.
+ * scale    multiplies the scores before the softmax (the caller's fp32 value, e.g. 1/sqrt(128))
+ * out      DEVICE  bf16 [batch, q_len, n_q_heads, head_dim]
+ * lse      DEVICE  fp32 [batch, q_len, n_q_heads], natural log; may be NULL
+ * stream   hipStream_t (NULL = the default stream).  The call only enqueues work: it never
+ *          synchronises and never reads device memory on the host.
+ *
+ * Ownership: the caller owns every buffer and keeps it alive and unmodified until the enqueued work
+ * has finished.  The library's workspace (see below) is shared by all calls on a device, so calls
+ * on different streams of one device must not overlap in time.  On failure nothing is enqueued.
+ */
+int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_ptrs,
+                 const int32_t* kv_lens, int batch, int q_len, int n_q_heads, int n_kv_heads,
+                 int head_dim, float scale, void* out, float* lse, void* stream);
+
+/*
+ * Workspace for the partial results of split sequences (section 4.4.3: the parts of a split
+ * sequence are computed by different compute units and aggregated afterwards).
+ * xattn_workspace_bytes: upper bound on the bytes one xattn_decode call of this shape uses.
+ * xattn_set_workspace:   hand the library a DEVICE buffer (256-byte aligned) for the current
+ *                        device; the caller keeps ownership and keeps it alive while calls are in
+ *                        flight.  (NULL, 0) returns to the library-owned workspace, which grows
+ *                        with hipMalloc on the first call that needs more (that call synchronises
+ *                        the device once to retire the old one).
+ */
+size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim);
+int xattn_set_workspace(void* dev_ptr, size_t bytes);
+
+/*
+ * Tuning knobs of the partition (section 4.4.3 Layer 3), for sweeps and for tests that show the
+ * result does not depend on the partition.  key:
+ *   XATTN_CFG_PIECES            number of equal-token pieces the batch's keys are cut into
+ *                               (= workgroups launched); 0 = automatic (a multiple of the CU count)
+ *   XATTN_CFG_MIN_PIECE_TOKENS  lower bound on a piece's tokens; 0 = default (64)
+ *   XATTN_CFG_TIMING            1 = record per-kernel events (see xattn_timing_read); 0 = off
+ * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
+ */
+enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2 };
+int xattn_configure(int key, int value);
+
+/*
+ * Per-kernel timing for benchmarks.  While XATTN_CFG_TIMING is 1, every xattn_decode call records
+ * HIP events on its stream before the split-KV decode kernel, between it and the merge kernel, and
+ * after the merge kernel (at most 4096 calls between two reads; later calls are not timed).
+ * xattn_timing_read waits for the recorded events, returns the number of timed calls since the last
+ * read and the SUMS of the two kernels' durations in milliseconds (HOST outputs, any may be NULL),
+ * and starts a new series.  Events cost a little time themselves: measure whole-call throughput
+ * with timing off.
+ */
+int xattn_timing_read(int* n_calls, float* decode_kernel_ms, float* merge_kernel_ms);
+
+/*
+ * xTensor range (section 4.3): reserve `reserve_bytes` of virtual address space for one tensor of
+ * one request (the paper's MaxSeqLen worth), unbacked, then back its first `mapped_bytes` with
+ * physical chunks of XTENSOR_CHUNK_BYTES each, created one by one and mapped in a pseudo-random
+ * order drawn from `seed` (so that neighbouring virtual chunks are not physically adjacent), and
+ * make them readable and writable from `device`.  Both sizes are rounded up to whole chunks;
+ * mapped_bytes may be 0 and must not exceed reserve_bytes.
+ *
+ * base_out   HOST out: DEVICE virtual address of the range's first byte (chunk-aligned)
+ * handle_out HOST out: opaque handle, owned by the library until xtensor_unmap
+ * Errors: XATTN_EINVAL (sizes, null outputs), XATTN_EUNSUPPORTED (the device's mapping granularity
+ * does not divide the chunk size), XATTN_ENOMEM, XATTN_EHIP.  On failure everything already
+ * created is released again and the outputs are left NULL.
+ */
+#define XTENSOR_CHUNK_BYTES ((size_t)2 << 20)
+int xtensor_map(size_t reserve_bytes, size_t mapped_bytes, uint64_t seed, int device,
+                void** base_out, void** handle_out);
+
+/* Unmap every chunk, release the physical memory and free the virtual range.  The caller makes
+ * sure no kernel still uses the range.  A handle that is NULL or was already unmapped gives
+ * XATTN_EINVAL and changes nothing. */
+int xtensor_unmap(void* handle);
+
+/*
+ * Description of a mapped range, for tests of the address identity of section 4.3
+ * (page = floor((va - va_start) / page_size), offset = (va - va_start) mod page_size):
+ * order_out[i] (HOST int32[n], n >= mapped chunk count) receives the creation index of the
+ * physical chunk that backs virtual chunk i.  Returns the mapped chunk count, or a negative status.
+ */
+int xtensor_chunk_order(void* handle, int32_t* order_out, int n);
+
+/*
+ * A second, read-write view of the physical chunks of `handle` in creation order (virtual chunk i of
+ * the view is physical chunk i): the same memory under another address, which lets a test read back
+ * through physical order what it wrote through the permuted range.  The view is owned by the
+ * handle and disappears with xtensor_unmap.  view_out: HOST out, DEVICE address.
+ */
+int xtensor_physical_view(void* handle, void** view_out);
+
+/* Synchronous copies between HOST memory and any DEVICE address (mapped ranges included). */
+int xtensor_upload(void* dst_device, const void* src_host, size_t bytes);
+int xtensor_download(void* dst_host, const void* src_device, size_t bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XATTN_H_ */

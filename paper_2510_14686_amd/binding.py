@@ -1,0 +1,160 @@
+"""ctypes binding of libxattn.so: the same names and arguments as include/xattn.h.
+
+Argument marshalling only -- every step of the path runs in the library's kernels.  Device
+pointers may be given as integers or as torch tensors (their ``data_ptr()`` is taken).  There is
+no fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+XATTN_OK, XATTN_EINVAL, XATTN_EUNSUPPORTED, XATTN_ENOMEM, XATTN_EHIP = 0, -1, -2, -3, -4
+XATTN_CFG_PIECES, XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_TIMING = 0, 1, 2
+XTENSOR_CHUNK_BYTES = 2 << 20
+
+EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_set_workspace",
+           "xattn_configure", "xattn_timing_read", "xtensor_map", "xtensor_unmap", "xtensor_chunk_order",
+           "xtensor_physical_view", "xtensor_upload", "xtensor_download"]
+
+
+class XattnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__("xattn status %d: %s" % (status, message))
+        self.status = status
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libxattn.so (building it only if no built library exists)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or _build.LIB_PATH
+    if not os.path.exists(p):
+        p = _build.build()
+    lib = ctypes.CDLL(p)
+    vp, i32, sz, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint64
+    lib.xattn_last_error.restype = ctypes.c_char_p
+    lib.xattn_last_error.argtypes = []
+    lib.xattn_decode.restype = i32
+    lib.xattn_decode.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    lib.xattn_workspace_bytes.restype = sz
+    lib.xattn_workspace_bytes.argtypes = [i32] * 5
+    lib.xattn_set_workspace.restype = i32
+    lib.xattn_set_workspace.argtypes = [vp, sz]
+    lib.xattn_configure.restype = i32
+    lib.xattn_configure.argtypes = [i32, i32]
+    lib.xattn_timing_read.restype = i32
+    lib.xattn_timing_read.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float),
+                                      ctypes.POINTER(ctypes.c_float)]
+    lib.xtensor_map.restype = i32
+    lib.xtensor_map.argtypes = [sz, sz, u64, i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.xtensor_unmap.restype = i32
+    lib.xtensor_unmap.argtypes = [vp]
+    lib.xtensor_chunk_order.restype = i32
+    lib.xtensor_chunk_order.argtypes = [vp, vp, i32]
+    lib.xtensor_physical_view.restype = i32
+    lib.xtensor_physical_view.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.xtensor_upload.restype = i32
+    lib.xtensor_upload.argtypes = [vp, vp, sz]
+    lib.xtensor_download.restype = i32
+    lib.xtensor_download.argtypes = [vp, vp, sz]
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _ptr(x) -> Optional[int]:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return int(x.data_ptr())
+    raise TypeError("expected an integer address or a tensor, got %r" % type(x))
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise XattnError(status, xattn_last_error())
+    return status
+
+
+def xattn_last_error() -> str:
+    return load_library().xattn_last_error().decode("utf-8", "replace")
+
+
+def xattn_decode(q, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, scale: float, out, lse=None, stream=None) -> None:
+    """Enqueue decode attention; see include/xattn.h.  All pointers are device addresses."""
+    if stream is not None and not isinstance(stream, int):
+        stream = int(stream.cuda_stream)
+    _check(load_library().xattn_decode(_ptr(q), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(kv_lens), batch, q_len,
+                                       n_q_heads, n_kv_heads, head_dim, ctypes.c_float(scale), _ptr(out),
+                                       _ptr(lse), stream))
+
+
+def xattn_workspace_bytes(batch: int, q_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:
+    n = int(load_library().xattn_workspace_bytes(batch, q_len, n_q_heads, n_kv_heads, head_dim))
+    if n == 0:
+        raise XattnError(XATTN_EUNSUPPORTED, xattn_last_error())
+    return n
+
+
+def xattn_set_workspace(dev_ptr, nbytes: int) -> None:
+    _check(load_library().xattn_set_workspace(_ptr(dev_ptr), nbytes))
+
+
+def xattn_configure(key: int, value: int) -> None:
+    _check(load_library().xattn_configure(key, value))
+
+
+def xattn_timing_read() -> Tuple[int, float, float]:
+    """(timed calls, sum of decode-kernel ms, sum of merge-kernel ms) since the last read."""
+    n, a, b = ctypes.c_int(), ctypes.c_float(), ctypes.c_float()
+    _check(load_library().xattn_timing_read(ctypes.byref(n), ctypes.byref(a), ctypes.byref(b)))
+    return int(n.value), float(a.value), float(b.value)
+
+
+def xtensor_map(reserve_bytes: int, mapped_bytes: int, seed: int, device: int) -> Tuple[int, int]:
+    """Returns (base device address, handle)."""
+    base, handle = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(load_library().xtensor_map(reserve_bytes, mapped_bytes, seed, device, ctypes.byref(base),
+                                      ctypes.byref(handle)))
+    return int(base.value), int(handle.value)
+
+
+def xtensor_unmap(handle: int) -> None:
+    _check(load_library().xtensor_unmap(handle))
+
+
+def xtensor_chunk_order(handle: int) -> np.ndarray:
+    lib = load_library()
+    # ask with a generous buffer: a range of MaxSeqLen tokens has at most a few thousand chunks
+    buf = np.empty(1 << 16, dtype=np.int32)
+    n = _check(lib.xtensor_chunk_order(handle, buf.ctypes.data, buf.size))
+    return buf[:n].copy()
+
+
+def xtensor_physical_view(handle: int) -> int:
+    view = ctypes.c_void_p()
+    _check(load_library().xtensor_physical_view(handle, ctypes.byref(view)))
+    return int(view.value)
+
+
+def xtensor_upload(dst_device: int, src: np.ndarray) -> None:
+    src = np.ascontiguousarray(src)
+    _check(load_library().xtensor_upload(dst_device, src.ctypes.data, src.nbytes))
+
+
+def xtensor_download(dst: np.ndarray, src_device: int) -> None:
+    assert dst.flags["C_CONTIGUOUS"]
+    _check(load_library().xtensor_download(dst.ctypes.data, src_device, dst.nbytes))

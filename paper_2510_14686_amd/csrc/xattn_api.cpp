@@ -1,0 +1,265 @@
+// C-ABI entry points of libxattn.so: argument checks, workspace, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <mutex>
+#include <vector>
+
+#include "../../include/xattn.h"
+#include "xattn_internal.h"
+#include "xattn_kernels.h"
+
+namespace xattn {
+
+static thread_local char g_error[512] = "";
+
+int fail(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+    const int status = (e == hipErrorOutOfMemory) ? XATTN_ENOMEM : XATTN_EHIP;
+    return fail(status, "%s failed: %s (%d)", what, hipGetErrorString(e), (int)e);
+}
+
+namespace {
+
+constexpr int kMaxDevices = 16;
+constexpr int kMaxBatch = 4096;
+constexpr int kMaxQLen = 16;
+constexpr int kMaxRows = 64;
+constexpr int kDefaultMinPieceTokens = 64;
+
+struct DeviceState {
+    int n_cu = 0;
+    void* owned_ws = nullptr;    // library-owned workspace
+    size_t owned_bytes = 0;
+    void* user_ws = nullptr;     // caller-provided workspace, if any
+    size_t user_bytes = 0;
+};
+
+std::mutex g_mutex;
+DeviceState g_dev[kMaxDevices];
+int g_cfg_pieces = 0;
+int g_cfg_min_piece = 0;
+int g_cfg_timing = 0;
+
+constexpr int kMaxTimedCalls = 4096;
+std::vector<hipEvent_t> g_events;     // three per timed call, created on demand, reused across series
+int g_timed_calls = 0;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int pieces_for(int n_cu) { return g_cfg_pieces > 0 ? g_cfg_pieces : 4 * n_cu; }
+
+struct WorkspaceLayout {
+    size_t meta_off, ml_off, o_off, total;
+};
+
+WorkspaceLayout layout_for(int batch, int q_len, int n_q_heads, int n_pieces) {
+    const size_t slots = (size_t)n_pieces + (size_t)batch;
+    const size_t rows = (size_t)q_len * (size_t)n_q_heads;
+    WorkspaceLayout w;
+    w.meta_off = 0;
+    w.ml_off = align_up((size_t)(kMetaCum + batch) * sizeof(int32_t), 256);
+    w.o_off = w.ml_off + align_up(slots * rows * 2 * sizeof(float), 256);
+    w.total = w.o_off + align_up(slots * rows * kHeadDim * sizeof(float), 256);
+    return w;
+}
+
+int check_shape(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim) {
+    if (batch < 1 || q_len < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1)
+        return fail(XATTN_EINVAL, "batch, q_len, n_q_heads, n_kv_heads and head_dim must be positive");
+    if (n_q_heads % n_kv_heads != 0)
+        return fail(XATTN_EUNSUPPORTED, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", n_q_heads, n_kv_heads);
+    if (head_dim != kHeadDim) return fail(XATTN_EUNSUPPORTED, "head_dim %d: only 128 is supported", head_dim);
+    if (batch > kMaxBatch) return fail(XATTN_EUNSUPPORTED, "batch %d exceeds %d", batch, kMaxBatch);
+    if (q_len > kMaxQLen) return fail(XATTN_EUNSUPPORTED, "q_len %d exceeds %d", q_len, kMaxQLen);
+    if ((n_q_heads / n_kv_heads) * q_len > kMaxRows)
+        return fail(XATTN_EUNSUPPORTED, "(n_q_heads / n_kv_heads) * q_len = %d exceeds %d",
+                    (n_q_heads / n_kv_heads) * q_len, kMaxRows);
+    return XATTN_OK;
+}
+
+int device_state(DeviceState** out, int* dev_out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(XATTN_EUNSUPPORTED, "device index %d not supported", dev);
+    DeviceState& d = g_dev[dev];
+    if (d.n_cu == 0) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute(MultiprocessorCount)");
+        d.n_cu = n > 0 ? n : 256;
+    }
+    *out = &d;
+    if (dev_out) *dev_out = dev;
+    return XATTN_OK;
+}
+
+}  // namespace
+}  // namespace xattn
+
+using namespace xattn;
+
+extern "C" {
+
+const char* xattn_last_error(void) { return g_error; }
+
+int xattn_configure(int key, int value) {
+    if (value < 0 || value > 65536) return fail(XATTN_EINVAL, "xattn_configure: value %d outside [0, 65536]", value);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    switch (key) {
+        case XATTN_CFG_PIECES: g_cfg_pieces = value; return XATTN_OK;
+        case XATTN_CFG_MIN_PIECE_TOKENS: g_cfg_min_piece = value; return XATTN_OK;
+        case XATTN_CFG_TIMING: g_cfg_timing = value ? 1 : 0; return XATTN_OK;
+        default: return fail(XATTN_EINVAL, "xattn_configure: unknown key %d", key);
+    }
+}
+
+size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim) {
+    if (check_shape(batch, q_len, n_q_heads, n_kv_heads, head_dim) != XATTN_OK) return 0;
+    // Upper bound over the automatic piece count of any supported device and the configured one.
+    int pieces = g_cfg_pieces > 0 ? g_cfg_pieces : 4 * 256;
+    DeviceState* d = nullptr;
+    if (g_cfg_pieces == 0 && device_state(&d, nullptr) == XATTN_OK) pieces = pieces_for(d->n_cu);
+    return layout_for(batch, q_len, n_q_heads, pieces).total;
+}
+
+int xattn_set_workspace(void* dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0))
+        return fail(XATTN_EINVAL, "xattn_set_workspace: pointer and size must both be given or both be zero");
+    if (reinterpret_cast<uintptr_t>(dev_ptr) % 256 != 0)
+        return fail(XATTN_EINVAL, "xattn_set_workspace: pointer is not 256-byte aligned");
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* d = nullptr;
+    int st = device_state(&d, nullptr);
+    if (st != XATTN_OK) return st;
+    d->user_ws = dev_ptr;
+    d->user_bytes = bytes;
+    return XATTN_OK;
+}
+
+int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_ptrs, const int32_t* kv_lens,
+                 int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim, float scale, void* out,
+                 float* lse, void* stream) {
+    if (!q || !k_ptrs || !v_ptrs || !kv_lens || !out)
+        return fail(XATTN_EINVAL, "xattn_decode: q, k_ptrs, v_ptrs, kv_lens and out must not be NULL");
+    int st = check_shape(batch, q_len, n_q_heads, n_kv_heads, head_dim);
+    if (st != XATTN_OK) return st;
+    if (!std::isfinite(scale)) return fail(XATTN_EINVAL, "xattn_decode: scale is not finite");
+    if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
+        return fail(XATTN_EINVAL, "xattn_decode: q and out must be 16-byte aligned");
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* d = nullptr;
+    st = device_state(&d, nullptr);
+    if (st != XATTN_OK) return st;
+
+    const int n_pieces = pieces_for(d->n_cu);
+    const WorkspaceLayout w = layout_for(batch, q_len, n_q_heads, n_pieces);
+    char* ws = nullptr;
+    if (d->user_ws) {
+        if (d->user_bytes < w.total)
+            return fail(XATTN_ENOMEM, "xattn_decode: caller workspace has %zu bytes, this call needs %zu",
+                        d->user_bytes, w.total);
+        ws = static_cast<char*>(d->user_ws);
+    } else {
+        if (d->owned_bytes < w.total) {
+            // Work enqueued earlier may still use the old buffer: retire it before freeing.
+            hipError_t e = hipDeviceSynchronize();
+            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+            if (d->owned_ws) (void)hipFree(d->owned_ws);
+            d->owned_ws = nullptr;
+            d->owned_bytes = 0;
+            const size_t want = w.total + w.total / 4;
+            e = hipMalloc(&d->owned_ws, want);
+            if (e != hipSuccess) {
+                d->owned_ws = nullptr;
+                return fail_hip(e, "hipMalloc(workspace)");
+            }
+            d->owned_bytes = want;
+        }
+        ws = static_cast<char*>(d->owned_ws);
+    }
+
+    DecodeParams prm;
+    prm.q = static_cast<const uint16_t*>(q);
+    prm.k_ptrs = k_ptrs;
+    prm.v_ptrs = v_ptrs;
+    prm.kv_lens = kv_lens;
+    prm.batch = batch;
+    prm.q_len = q_len;
+    prm.n_q_heads = n_q_heads;
+    prm.n_kv_heads = n_kv_heads;
+    prm.group = n_q_heads / n_kv_heads;
+    prm.scale_log2 = (float)((double)scale * 1.4426950408889634074);
+    prm.out = static_cast<uint16_t*>(out);
+    prm.lse = lse;
+    prm.meta = reinterpret_cast<int32_t*>(ws + w.meta_off);
+    prm.part_ml = reinterpret_cast<float*>(ws + w.ml_off);
+    prm.part_o = reinterpret_cast<float*>(ws + w.o_off);
+    prm.n_pieces = n_pieces;
+    prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
+
+    hipEvent_t* events = nullptr;
+    if (g_cfg_timing && g_timed_calls < kMaxTimedCalls) {
+        while ((int)g_events.size() < 3 * (g_timed_calls + 1)) {
+            hipEvent_t ev;
+            hipError_t ee = hipEventCreate(&ev);
+            if (ee != hipSuccess) return fail_hip(ee, "hipEventCreate");
+            g_events.push_back(ev);
+        }
+        events = &g_events[3 * g_timed_calls];
+    }
+    hipError_t e = launch_decode(prm, static_cast<hipStream_t>(stream), events);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (events) ++g_timed_calls;
+    return XATTN_OK;
+}
+
+int xattn_timing_read(int* n_calls, float* decode_kernel_ms, float* merge_kernel_ms) {
+    std::lock_guard<std::mutex> lock(g_mutex);
+    float decode_ms = 0.0f, merge_ms = 0.0f;
+    for (int i = 0; i < g_timed_calls; ++i) {
+        hipError_t e = hipEventSynchronize(g_events[3 * i + 2]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventSynchronize");
+        float a = 0.0f, b = 0.0f;
+        e = hipEventElapsedTime(&a, g_events[3 * i], g_events[3 * i + 1]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+        e = hipEventElapsedTime(&b, g_events[3 * i + 1], g_events[3 * i + 2]);
+        if (e != hipSuccess) return fail_hip(e, "hipEventElapsedTime");
+        decode_ms += a;
+        merge_ms += b;
+    }
+    if (n_calls) *n_calls = g_timed_calls;
+    if (decode_kernel_ms) *decode_kernel_ms = decode_ms;
+    if (merge_kernel_ms) *merge_kernel_ms = merge_ms;
+    g_timed_calls = 0;
+    return XATTN_OK;
+}
+
+int xtensor_upload(void* dst_device, const void* src_host, size_t bytes) {
+    if (bytes == 0) return XATTN_OK;
+    if (!dst_device || !src_host) return fail(XATTN_EINVAL, "xtensor_upload: NULL pointer");
+    hipError_t e = hipMemcpy(dst_device, src_host, bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpy(host to device)");
+    return XATTN_OK;
+}
+
+int xtensor_download(void* dst_host, const void* src_device, size_t bytes) {
+    if (bytes == 0) return XATTN_OK;
+    if (!dst_host || !src_device) return fail(XATTN_EINVAL, "xtensor_download: NULL pointer");
+    hipError_t e = hipMemcpy(dst_host, src_device, bytes, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return fail_hip(e, "hipMemcpy(device to host)");
+    return XATTN_OK;
+}
+
+}  // extern "C"

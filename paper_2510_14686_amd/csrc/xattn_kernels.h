@@ -1,0 +1,43 @@
+// Internal interface between the C-ABI host code and the gfx950 kernels.
+#ifndef XATTN_KERNELS_H_
+#define XATTN_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace xattn {
+
+constexpr int kHeadDim = 128;
+constexpr int kMaxWavesPerBlock = 8;   // one wave per KV head, up to 8 KV heads per workgroup
+
+// Workspace header (int32 words): total tokens, tokens per piece, then the exclusive prefix sums of
+// the clamped kv_lens.
+constexpr int kMetaTotal = 0;
+constexpr int kMetaPiece = 1;
+constexpr int kMetaCum = 2;
+
+struct DecodeParams {
+    const uint16_t* q;               // bf16 [batch, q_len, n_q_heads, 128]
+    const void* const* k_ptrs;       // device array[batch] of device pointers
+    const void* const* v_ptrs;
+    const int32_t* kv_lens;          // device int32[batch]
+    int batch, q_len, n_q_heads, n_kv_heads, group;
+    float scale_log2;                // scale * log2(e)
+    uint16_t* out;                   // bf16 [batch, q_len, n_q_heads, 128]
+    float* lse;                      // fp32 [batch, q_len, n_q_heads] or null
+    float* part_o;                   // fp32 [slots, q_len * n_q_heads, 128]
+    float* part_ml;                  // fp32 [slots, q_len * n_q_heads, 2]  (max, sum)
+    int32_t* meta;                   // int32 [2 + batch]
+    int n_pieces;                    // pieces the token stream is cut into (upper bound on active ones)
+    int min_piece_tokens;
+};
+
+// Query rows one workgroup pass handles for a KV head with rows_total = group * q_len rows.
+int rows_per_tile(int rows_total);
+
+// Enqueues the split-KV decode kernel and the merge kernel on `stream`.  If `events` is not null it
+// holds three events, recorded before the decode kernel, between the kernels and after the merge.
+hipError_t launch_decode(const DecodeParams& prm, hipStream_t stream, hipEvent_t* events);
+
+}  // namespace xattn
+#endif

@@ -1,0 +1,52 @@
+"""The C-ABI library loads and exports every symbol include/xattn.h declares (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "xattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(x(?:attn|tensor)_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = _declared_functions()
+    for must in ("xattn_decode", "xtensor_map", "xtensor_unmap", "xattn_last_error"):
+        assert must in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2510_14686_amd import binding
+    lib = binding.load_library()
+    for name in _declared_functions():
+        assert hasattr(lib, name), "libxattn.so does not export %s" % name
+    assert sorted(binding.EXPORTS) == _declared_functions()
+
+
+def test_argument_checks_need_no_gpu():
+    """Calls rejected before any GPU work: they only run host code."""
+    from paper_2510_14686_amd import binding
+    with pytest.raises(binding.XattnError) as e:
+        binding.xattn_decode(0, 0, 0, 0, 1, 1, 8, 2, 128, 0.1, 0)
+    assert e.value.status == binding.XATTN_EINVAL
+    for args, status in (((1, 1, 8, 3, 128), binding.XATTN_EUNSUPPORTED),      # heads not divisible
+                         ((1, 1, 8, 2, 64), binding.XATTN_EUNSUPPORTED),       # head_dim
+                         ((0, 1, 8, 2, 128), binding.XATTN_EINVAL),            # batch
+                         ((1, 17, 8, 2, 128), binding.XATTN_EUNSUPPORTED),     # q_len
+                         ((1, 16, 40, 8, 128), binding.XATTN_EUNSUPPORTED)):   # 5 * 16 rows > 64
+        with pytest.raises(binding.XattnError) as e:
+            binding.xattn_decode(16, 16, 16, 16, *args, 0.1, 16)
+        assert e.value.status == status, (args, str(e.value))
+        assert binding.xattn_last_error()
+    with pytest.raises(binding.XattnError):
+        binding.xattn_configure(99, 1)
+    with pytest.raises(binding.XattnError):
+        binding.xattn_configure(binding.XATTN_CFG_PIECES, -1)
+    with pytest.raises(binding.XattnError) as e:
+        binding.xtensor_unmap(0)
+    assert e.value.status == binding.XATTN_EINVAL

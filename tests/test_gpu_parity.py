@@ -1,0 +1,151 @@
+"""HIP path (through the C ABI) against the fp64 CPU oracle, element by element, on seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from workloads import CONFIGS, normal_bf16
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+SCALE = float(np.float32(1.0 / math.sqrt(D)))
+
+
+def _rand_case(seed, lens, T, Hq, Hkv, extra_rows=0):
+    B = len(lens)
+    q = normal_bf16(seed, 0, B * T * Hq * D).reshape(B, T, Hq, D)
+    ks = [normal_bf16(seed, 1 + 2 * b, (L + extra_rows) * Hkv * D).reshape(L + extra_rows, Hkv, D)
+          for b, L in enumerate(lens)]
+    vs = [normal_bf16(seed, 2 + 2 * b, (L + extra_rows) * Hkv * D).reshape(L + extra_rows, Hkv, D)
+          for b, L in enumerate(lens)]
+    return q, ks, vs
+
+
+@pytest.fixture(autouse=True)
+def _default_partition():
+    import paper_2510_14686_amd as xa
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    yield
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+
+
+def test_tiny_config():
+    """Workload 'tiny' exactly: batch 4, 8/2 heads, KV lengths 17/64/100/256, seed 0."""
+    from gpu_util import check_against_oracle
+    w = CONFIGS["tiny"]
+    ks, vs = w.make_kv()
+    check_against_oracle(w.make_q(), ks, vs, w.kv_lens(), w.scale, what="tiny")
+
+
+@pytest.mark.parametrize("name,batch,div", [("qwen3_8b_decode", 12, 4), ("long_context", 3, 16),
+                                            ("spec_verify", 10, 8), ("skewed_xtensor", 40, 4)])
+def test_scaled_down_configs(name, batch, div):
+    """The four large workloads with fewer sequences and shorter lengths, every element checked.
+    Lengths still span many 16-key blocks, several pieces and ragged tails."""
+    from gpu_util import check_against_oracle
+    w = CONFIGS[name].scaled(name + "_small", batch, div)
+    lens = w.kv_lens()
+    ks, vs = w.make_kv(lens)
+    check_against_oracle(w.make_q(), ks, vs, lens, w.scale, what=w.name, xtensor=w.xtensor, seed=w.seed)
+
+
+@pytest.mark.parametrize("T", [1, 2, 3, 4])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 4), (5, 1), (7, 1), (16, 2), (12, 2), (6, 2), (32, 16)])
+def test_head_and_token_shapes(T, Hq, Hkv):
+    """GQA groups 1..8, 1..16 KV heads (more than 8 spills into a second workgroup set), 1..4 new
+    tokens with the causal mask; rows = group * T runs from 1 to 32 (above 16: two row tiles)."""
+    from gpu_util import check_against_oracle
+    lens = [T, T + 1, 15 + T, 16 + T, 17 + T, 63, 64, 65, 200, 333]
+    q, ks, vs = _rand_case(100 + T, lens, T, Hq, Hkv)
+    check_against_oracle(q, ks, vs, lens, SCALE, what="T=%d Hq=%d Hkv=%d" % (T, Hq, Hkv))
+
+
+def test_single_key_and_short_sequences():
+    from gpu_util import check_against_oracle
+    lens = [1, 1, 2, 3, 4, 5, 15, 16, 17]
+    q, ks, vs = _rand_case(7, lens, 1, 8, 2)
+    (max_abs, _, _, lse_err), out_bits, lse = check_against_oracle(q, ks, vs, lens, SCALE, what="short")
+    # kv_len = 1: the output is exactly the V row (bf16 in, bf16 out)
+    for b in (0, 1):
+        for h in range(8):
+            np.testing.assert_array_equal(out_bits[b, 0, h], vs[b][0, h // 4])
+
+
+def test_rows_past_kv_len_are_not_read():
+    """Buffers longer than kv_len hold NaN past the end: a read of them would poison the result."""
+    from gpu_util import gpu_attn, assert_parity
+    lens = [5, 16, 37, 100]
+    q, ks, vs = _rand_case(8, lens, 2, 8, 2, extra_rows=40)
+    for b, L in enumerate(lens):
+        ks[b][L:] = 0x7FC0
+        vs[b][L:] = 0x7FC0
+    out_bits, lse = gpu_attn(q, ks, vs, lens, SCALE)
+    ref_out, ref_lse = oracle.attn(q, [k[:L] for k, L in zip(ks, lens)], [v[:L] for v, L in zip(vs, lens)],
+                                   lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, what="padded buffers")
+
+
+@pytest.mark.parametrize("pieces,min_piece", [(8, 16), (64, 16), (1024, 16), (4096, 16), (1, 0), (37, 48)])
+def test_result_does_not_depend_on_the_partition(pieces, min_piece):
+    """Any cut of the key stream into pieces gives the same result up to fp32 re-association
+    (section 4.4.3: splitting a long sequence over compute units is exact)."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import gpu_attn, assert_parity
+    lens = [700, 33, 2, 2049, 16, 512, 90]
+    q, ks, vs = _rand_case(9, lens, 2, 8, 2)
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, SCALE)
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, pieces)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, min_piece)
+    out_bits, lse = gpu_attn(q, ks, vs, lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, what="pieces=%d" % pieces)
+
+
+def test_xtensor_and_plain_allocations_give_identical_bits():
+    """The kernel sees only a starting address (section 4.3, Operator Adaptation): the same bytes in
+    randomly permuted 2 MiB chunks and in an ordinary allocation give bit-identical results."""
+    from gpu_util import gpu_attn
+    lens = [3000, 1025, 40, 2048]          # 2048 B per token row: 1024 tokens per chunk
+    q, ks, vs = _rand_case(10, lens, 1, 16, 8)
+    a_out, a_lse = gpu_attn(q, ks, vs, lens, SCALE, xtensor=False)
+    b_out, b_lse = gpu_attn(q, ks, vs, lens, SCALE, xtensor=True, seed=5)
+    c_out, c_lse = gpu_attn(q, ks, vs, lens, SCALE, xtensor=True, seed=6)
+    np.testing.assert_array_equal(a_out, b_out)
+    np.testing.assert_array_equal(a_lse, b_lse)
+    np.testing.assert_array_equal(a_out, c_out)
+
+
+def test_causal_block_equals_sequential_calls_on_gpu():
+    """q_len = 4 in one call against four q_len = 1 calls with growing kv_len (section 4.4.1)."""
+    from gpu_util import gpu_attn
+    lens = [40, 4, 300, 77]
+    T = 4
+    q, ks, vs = _rand_case(11, lens, T, 8, 2)
+    out4, lse4 = gpu_attn(q, ks, vs, lens, SCALE)
+    for t in range(T):
+        lens_t = [L - T + t + 1 for L in lens]
+        out1, lse1 = gpu_attn(np.ascontiguousarray(q[:, t:t + 1]), ks, vs, lens_t, SCALE)
+        a = wl.bf16_to_f32(out4[:, t]).astype(np.float64)
+        b = wl.bf16_to_f32(out1[:, 0]).astype(np.float64)
+        assert np.max(np.abs(a - b)) <= 2e-2 * max(1.0, np.max(np.abs(b))) * 2 ** -6   # a bf16 ulp or two
+        assert np.max(np.abs(lse4[:, t] - lse1[:, 0])) < 1e-4
+
+
+def test_lse_may_be_null_and_kv_len_below_q_len():
+    from gpu_util import gpu_attn
+    lens = [2, 50]
+    T = 4                                   # sequence 0 has fewer keys than new tokens
+    q, ks, vs = _rand_case(12, [4, 50], T, 4, 2)
+    out_bits, lse = gpu_attn(q, ks, vs, lens, SCALE)
+    # tokens 0 and 1 of sequence 0 see no key: out = 0, lse = -inf; tokens 2, 3 see 1 and 2 keys
+    assert np.all(out_bits[0, :2] == 0) and np.all(np.isneginf(lse[0, :2]))
+    ref_out, ref_lse = oracle.attn(q[:, 2:], [ks[0][:2], ks[1]], [vs[0][:2], vs[1]], [2, 50], SCALE)
+    from gpu_util import assert_parity
+    assert_parity(out_bits[:, 2:], lse[:, 2:], ref_out, ref_lse, what="kv_len < q_len tail")
+    out2, none = gpu_attn(q, ks, vs, lens, SCALE, want_lse=False)
+    assert none is None
+    np.testing.assert_array_equal(out2, out_bits)
