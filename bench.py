@@ -149,6 +149,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="qwen3_8b_decode")
     ap.add_argument("--only", action="store_true", help="measure only --workload, not the other large workloads")
+    ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
+    ap.add_argument("--min-piece-tokens", type=int, default=0, help="override the minimum piece size (0 = default)")
+    ap.add_argument("--path", type=int, default=0, help="inner loop: 0 automatic, 1 vector, 2 matrix cores")
     ap.add_argument("--check-sequences", type=int, default=None, help="sequences verified against the oracle (default all)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -166,6 +169,10 @@ def main():
     if not os.path.exists(xbuild.LIB_PATH):
         xbuild.build()
 
+    import paper_2510_14686_amd as xa
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, args.pieces)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, args.min_piece_tokens)
+    xa.xattn_configure(xa.XATTN_CFG_PATH, args.path)
     head = workloads.CONFIGS[args.workload]
     main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True)
     others = {}

@@ -94,12 +94,15 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  * Tuning knobs of the partition (section 4.4.3 Layer 3), for sweeps and for tests that show the
  * result does not depend on the partition.  key:
  *   XATTN_CFG_PIECES            number of equal-token pieces the batch's keys are cut into
- *                               (= workgroups launched); 0 = automatic (a multiple of the CU count)
+ *                               (= workgroups launched); 0 = automatic (the CU count)
  *   XATTN_CFG_MIN_PIECE_TOKENS  lower bound on a piece's tokens; 0 = default (64)
  *   XATTN_CFG_TIMING            1 = record per-kernel events (see xattn_timing_read); 0 = off
+ *   XATTN_CFG_PATH              inner loop of the decode kernel: 0 = automatic (vector path below 4
+ *                               query rows per KV head, i.e. group * q_len < 4; matrix-core path
+ *                               from 4 up), 1 = vector path, 2 = matrix-core path (section 4.4.1)
  * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
  */
-enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2 };
+enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3 };
 int xattn_configure(int key, int value);
 
 /*

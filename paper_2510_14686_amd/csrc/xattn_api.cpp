@@ -49,6 +49,7 @@ DeviceState g_dev[kMaxDevices];
 int g_cfg_pieces = 0;
 int g_cfg_min_piece = 0;
 int g_cfg_timing = 0;
+int g_cfg_path = 0;
 
 constexpr int kMaxTimedCalls = 4096;
 std::vector<hipEvent_t> g_events;     // three per timed call, created on demand, reused across series
@@ -56,7 +57,7 @@ int g_timed_calls = 0;
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-int pieces_for(int n_cu) { return g_cfg_pieces > 0 ? g_cfg_pieces : 4 * n_cu; }
+int pieces_for(int n_cu) { return g_cfg_pieces > 0 ? g_cfg_pieces : n_cu; }
 
 struct WorkspaceLayout {
     size_t meta_off, ml_off, o_off, total;
@@ -120,6 +121,10 @@ int xattn_configure(int key, int value) {
         case XATTN_CFG_PIECES: g_cfg_pieces = value; return XATTN_OK;
         case XATTN_CFG_MIN_PIECE_TOKENS: g_cfg_min_piece = value; return XATTN_OK;
         case XATTN_CFG_TIMING: g_cfg_timing = value ? 1 : 0; return XATTN_OK;
+        case XATTN_CFG_PATH:
+            if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: path %d is not 0, 1 or 2", value);
+            g_cfg_path = value;
+            return XATTN_OK;
         default: return fail(XATTN_EINVAL, "xattn_configure: unknown key %d", key);
     }
 }
@@ -127,7 +132,7 @@ int xattn_configure(int key, int value) {
 size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim) {
     if (check_shape(batch, q_len, n_q_heads, n_kv_heads, head_dim) != XATTN_OK) return 0;
     // Upper bound over the automatic piece count of any supported device and the configured one.
-    int pieces = g_cfg_pieces > 0 ? g_cfg_pieces : 4 * 256;
+    int pieces = g_cfg_pieces > 0 ? g_cfg_pieces : 256;
     DeviceState* d = nullptr;
     if (g_cfg_pieces == 0 && device_state(&d, nullptr) == XATTN_OK) pieces = pieces_for(d->n_cu);
     return layout_for(batch, q_len, n_q_heads, pieces).total;
@@ -208,6 +213,7 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
     prm.part_o = reinterpret_cast<float*>(ws + w.o_off);
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
+    prm.path = g_cfg_path;
 
     hipEvent_t* events = nullptr;
     if (g_cfg_timing && g_timed_calls < kMaxTimedCalls) {

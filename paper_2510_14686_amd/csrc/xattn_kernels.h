@@ -30,10 +30,18 @@ struct DecodeParams {
     int32_t* meta;                   // int32 [2 + batch]
     int n_pieces;                    // pieces the token stream is cut into (upper bound on active ones)
     int min_piece_tokens;
+    int path;                        // kPathAuto, kPathVector or kPathMatrix
 };
 
+// Inner-loop choice: automatic = vector path below 4 query rows per KV head, matrix path from 4 up.
+constexpr int kPathAuto = 0;
+constexpr int kPathVector = 1;
+constexpr int kPathMatrix = 2;
+
+bool use_matrix_path(int rows_total, int path);
+
 // Query rows one workgroup pass handles for a KV head with rows_total = group * q_len rows.
-int rows_per_tile(int rows_total);
+int rows_per_tile(int rows_total, int path);
 
 // Enqueues the split-KV decode kernel and the merge kernel on `stream`.  If `events` is not null it
 // holds three events, recorded before the decode kernel, between the kernels and after the merge.

@@ -9,11 +9,18 @@
 // that covers its whole sequence writes the final result; any other writes an un-normalised partial
 // (o, m, l) to slot piece + sequence_index, and the merge kernel combines a sequence's slots.
 //
-// Inner loop: 16 lanes hold one 256-byte K (or V) row, 8 bf16 each, loaded with one 128-bit load per
-// lane, so a wave load covers four rows.  All query rows that share the KV head (GQA group x new
-// tokens: section 4.4.1, K is loaded once for all of them and Q stays in registers) are multiplied
-// with the row in registers: q.k via bf16 dot2 into fp32, reduced over the 16 lanes with DPP;
-// softmax is online in fp32 in the log2 domain; p.v accumulates in fp32.
+// Loads: 16 lanes hold one 256-byte K (or V) row, 8 bf16 each, one 128-bit non-temporal buffer load
+// per lane, so a wave load covers four rows; the buffer descriptor's size is the sequence's byte
+// length, so a ragged last block reads zeros instead of memory past the sequence (which an xTensor
+// range may not have mapped).  All query rows that share the KV head (GQA group x new tokens:
+// section 4.4.1, K is loaded once for all of them and Q stays in registers) use the row from
+// registers.  Two inner loops:
+//   * vector path (up to 8 rows): q.k by bf16 dot2 into fp32, reduced over the 16 lanes with DPP;
+//     online softmax in fp32 (log2 domain); p.v by fp32 FMA.
+//   * matrix path (tiles of 16 rows, the multi-token verification case): the K block is transposed
+//     through wave-private LDS into the MFMA operand layout, S^T = K Q^T by bf16 MFMA 16x16x32;
+//     softmax on the accumulator layout (a lane holds 4 keys of one row); O^T += V^T P^T by fp32 MFMA
+//     16x16x4 straight from the V registers (p stays fp32, V never touches LDS).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,9 +31,14 @@ namespace {
 
 constexpr int kU = 4;                 // key rows per 16-lane group per block
 constexpr int kBlockKeys = 4 * kU;    // key rows per wave per block
+constexpr int kRowBytes = kHeadDim * 2;
 constexpr float kNegInf = -__builtin_inff();
+constexpr float kLn2 = 0.6931471805599453f;
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 // ---------------------------------------------------------------------------------- lane helpers
 template <int kCtrl>
@@ -71,6 +83,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Raw buffer descriptor over [base, base + bytes): loads past the end return 0.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+// 128-bit non-temporal load at base + voffset (per lane) + soffset (wave-uniform).
+__device__ __forceinline__ u32x4_t load_b128_nt(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
+    return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 2 /* nt */);
+}
+
 // ---------------------------------------------------------------------------------- the plan
 struct Plan {
     int total;      // N: tokens of the whole batch
@@ -98,7 +119,23 @@ __device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ kv_lens, i
     return pl;
 }
 
-// ---------------------------------------------------------------------------------- one segment
+// One (piece, sequence) intersection as seen by one wave.
+struct Segment {
+    int b, L;            // sequence and its length
+    int j0, j1;          // keys [j0, j1) of the sequence
+    int slot;            // partial-result slot (piece + sequence index)
+    bool whole;          // the segment is the whole sequence: write the final result
+    int kvh;             // this wave's KV head
+    int row0, n_rows;    // query rows [row0, row0 + n_rows) of the head's group * q_len rows
+};
+
+// Sequence length in bytes for the buffer descriptor (sequences of 4 GiB or more are not supported).
+__device__ __forceinline__ uint32_t seq_bytes(const DecodeParams& prm, int L) {
+    const unsigned long long b = (unsigned long long)L * (unsigned)prm.n_kv_heads * kRowBytes;
+    return b > 0xffffffffull ? 0xffffffffu : (uint32_t)b;
+}
+
+// ---------------------------------------------------------------------------------- vector path
 template <int R>
 struct RowState {
     float m[R];        // running max of the scaled scores, log2 domain
@@ -107,40 +144,27 @@ struct RowState {
 };
 
 struct KvBlock {
-    uint4 k[kU];
-    uint4 v[kU];
+    u32x4_t k[kU];
+    u32x4_t v[kU];
 };
 
-// Loads of a block whose rows all lie inside the segment.
-__device__ __forceinline__ void load_block(KvBlock& blk, const char* kbase, const char* vbase, long row_stride,
-                                           int j_first) {
+// Key rows j_first + 4u + (lane / 16), u = 0..3; soffset carries the wave-uniform part.
+__device__ __forceinline__ void load_block(KvBlock& blk, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
+                                           uint32_t voffset, uint32_t row_stride, int j_first) {
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
-        const long off = (long)(j_first + 4 * u) * row_stride;
-        blk.k[u] = *reinterpret_cast<const uint4*>(kbase + off);
-        blk.v[u] = *reinterpret_cast<const uint4*>(vbase + off);
-    }
-}
-// Loads of the ragged last block: rows past the segment's end re-read its last row (never memory
-// beyond the sequence, which may be unmapped) and are masked out of the scores by the caller.
-__device__ __forceinline__ void load_block_clamped(KvBlock& blk, const char* kbase, const char* vbase,
-                                                   long row_stride, int j_first, int j_last_valid) {
-#pragma unroll
-    for (int u = 0; u < kU; ++u) {
-        int j = j_first + 4 * u;
-        j = j < j_last_valid ? j : j_last_valid;
-        const long off = (long)j * row_stride;
-        blk.k[u] = *reinterpret_cast<const uint4*>(kbase + off);
-        blk.v[u] = *reinterpret_cast<const uint4*>(vbase + off);
+        const uint32_t so = (uint32_t)(j_first + 4 * u) * row_stride;
+        blk.k[u] = load_b128_nt(rk, voffset, so);
+        blk.v[u] = load_b128_nt(rv, voffset, so);
     }
 }
 
 // One block of kU key rows per 16-lane group against R query rows.
-// j_sub: absolute key index of this lane's row for u = 0 (rows u are 4 apart).  lim[r]: first key
+// j_sub: absolute key index of this lane's row for u = 0 (rows u are 4 apart).  lim_of(r): first key
 // index row r may NOT see (segment end and causal limit); used only when kMasked.
-template <int R, bool kMasked>
+template <int R, bool kMasked, typename LimFn>
 __device__ __forceinline__ void compute_block(RowState<R>& st, const KvBlock& blk, const uint32_t (&q)[R][4],
-                                              float scale_log2, int j_sub, const int (&lim)[R]) {
+                                              float scale_log2, int j_sub, LimFn lim_of) {
     float s[R][kU];
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
@@ -152,12 +176,10 @@ __device__ __forceinline__ void compute_block(RowState<R>& st, const KvBlock& bl
             acc = dot2_bf16(q[r][2], k2, acc);
             acc = dot2_bf16(q[r][3], k3, acc);
             acc = row16_sum(acc) * scale_log2;
-            if (kMasked) acc = (j_sub + 4 * u < lim[r]) ? acc : kNegInf;
+            if (kMasked) acc = (j_sub + 4 * u < lim_of(r)) ? acc : kNegInf;
             s[r][u] = acc;
         }
     }
-    float p[R][kU];
-    float alpha[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         float mb = s[r][0];
@@ -167,17 +189,17 @@ __device__ __forceinline__ void compute_block(RowState<R>& st, const KvBlock& bl
         // While a row has seen no key yet its max is -inf: subtract 0 instead so that exp2 sees
         // -inf (-> 0), not -inf - -inf.
         const float m_use = (kMasked && m_new == kNegInf) ? 0.0f : m_new;
-        alpha[r] = fast_exp2(st.m[r] - m_use);
+        const float alpha = fast_exp2(st.m[r] - m_use);
         float sum = 0.0f;
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
-            p[r][u] = fast_exp2(s[r][u] - m_use);
-            sum += p[r][u];
+            s[r][u] = fast_exp2(s[r][u] - m_use);
+            sum += s[r][u];
         }
-        st.l[r] = st.l[r] * alpha[r] + sum;
+        st.l[r] = st.l[r] * alpha + sum;
         st.m[r] = m_new;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st.o[r][e] *= alpha[r];
+        for (int e = 0; e < 8; ++e) st.o[r][e] *= alpha;
     }
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
@@ -189,37 +211,40 @@ __device__ __forceinline__ void compute_block(RowState<R>& st, const KvBlock& bl
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.o[r][e] = __builtin_fmaf(p[r][u], v[e], st.o[r][e]);
+            for (int e = 0; e < 8; ++e) st.o[r][e] = __builtin_fmaf(s[r][u], v[e], st.o[r][e]);
     }
 }
 
-// Keys [j0, j1) of sequence b (length L) for this wave's KV head and query rows [row0, row0 + n_rows)
-// of the head's G*T rows.  Rows r >= n_rows are padding: they repeat row 0 and are never stored.
+// Rows r >= seg.n_rows are padding: they repeat the tile's first row and are never stored.
 template <int R>
-__device__ __forceinline__ void process_segment(const DecodeParams& prm, int b, int L, int j0, int j1, int slot,
-                                                bool whole_sequence, int kvh, int row0, int n_rows, int lane) {
+__device__ __forceinline__ void vector_segment(const DecodeParams& prm, const Segment& seg, int lane) {
     const int sub = lane >> 4, ds = lane & 15;
     const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
-    const long row_stride = (long)prm.n_kv_heads * (kHeadDim * 2);
-    const char* kbase = static_cast<const char*>(prm.k_ptrs[b]) + (long)kvh * (kHeadDim * 2) + ds * 16;
-    const char* vbase = static_cast<const char*>(prm.v_ptrs[b]) + (long)kvh * (kHeadDim * 2) + ds * 16;
+    const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
+    const uint32_t voffset = (uint32_t)sub * row_stride + (uint32_t)seg.kvh * kRowBytes + ds * 16;
 
     // Q rows of this KV head: row r <-> (token t = r / G, head kvh*G + r % G); lane takes columns ds*8..+8.
+    auto row_token = [&](int r) { return (seg.row0 + (r < seg.n_rows ? r : 0)) / G; };
+    auto row_index = [&](int r) {      // row of [batch*T*Hq]
+        const int rr = seg.row0 + (r < seg.n_rows ? r : 0);
+        const int t = rr / G;
+        return (seg.b * T + t) * Hq + seg.kvh * G + (rr - t * G);
+    };
+    auto lim_of = [&](int r) {
+        const int causal = seg.L - T + row_token(r) + 1;
+        return causal < seg.j1 ? causal : seg.j1;
+    };
     uint32_t q[R][4];
-    int lim[R];
-    int qrow[R];    // row index into [batch*T*Hq]
-    int min_lim = j1;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        const int rr = row0 + (r < n_rows ? r : 0);
-        const int t = rr / G, g = rr - t * G;
-        qrow[r] = (b * T + t) * Hq + kvh * G + g;
-        const uint4 qv = *reinterpret_cast<const uint4*>(prm.q + (long)qrow[r] * kHeadDim + ds * 8);
+        const uint4 qv = *reinterpret_cast<const uint4*>(prm.q + (long)row_index(r) * kHeadDim + ds * 8);
         q[r][0] = qv.x; q[r][1] = qv.y; q[r][2] = qv.z; q[r][3] = qv.w;
-        const int causal = L - T + t + 1;
-        lim[r] = causal < j1 ? causal : j1;
-        min_lim = lim[r] < min_lim ? lim[r] : min_lim;
     }
+    // token 0 of the tile has the tightest causal limit
+    const int causal0 = seg.L - T + seg.row0 / G + 1;
+    const int min_lim = causal0 < seg.j1 ? causal0 : seg.j1;
 
     RowState<R> st;
 #pragma unroll
@@ -232,25 +257,23 @@ __device__ __forceinline__ void process_segment(const DecodeParams& prm, int b, 
 
     // Full blocks: every key visible to every row.  Two register buffers, the next block's loads are
     // issued before the current block's arithmetic.
-    const int n_full = min_lim > j0 ? (min_lim - j0) / kBlockKeys : 0;
-    const char* kb = kbase + (long)sub * row_stride;
-    const char* vb = vbase + (long)sub * row_stride;
+    const int n_full = min_lim > seg.j0 ? (min_lim - seg.j0) / kBlockKeys : 0;
     KvBlock A, Bk;
     int blk = 0;
     if (n_full > 0) {
-        load_block(A, kb, vb, row_stride, j0);
+        load_block(A, rk, rv, voffset, row_stride, seg.j0);
         for (; blk + 2 <= n_full; blk += 2) {
-            load_block(Bk, kb, vb, row_stride, j0 + (blk + 1) * kBlockKeys);
-            compute_block<R, false>(st, A, q, prm.scale_log2, 0, lim);
-            if (blk + 2 < n_full) load_block(A, kb, vb, row_stride, j0 + (blk + 2) * kBlockKeys);
-            compute_block<R, false>(st, Bk, q, prm.scale_log2, 0, lim);
+            load_block(Bk, rk, rv, voffset, row_stride, seg.j0 + (blk + 1) * kBlockKeys);
+            compute_block<R, false>(st, A, q, prm.scale_log2, 0, lim_of);
+            if (blk + 2 < n_full) load_block(A, rk, rv, voffset, row_stride, seg.j0 + (blk + 2) * kBlockKeys);
+            compute_block<R, false>(st, Bk, q, prm.scale_log2, 0, lim_of);
         }
-        if (blk < n_full) compute_block<R, false>(st, A, q, prm.scale_log2, 0, lim);
+        if (blk < n_full) compute_block<R, false>(st, A, q, prm.scale_log2, 0, lim_of);
     }
     // Ragged tail and the causally masked last keys.
-    for (int jt = j0 + n_full * kBlockKeys; jt < j1; jt += kBlockKeys) {
-        load_block_clamped(A, kbase, vbase, row_stride, jt + sub, j1 - 1);
-        compute_block<R, true>(st, A, q, prm.scale_log2, jt + sub, lim);
+    for (int jt = seg.j0 + n_full * kBlockKeys; jt < seg.j1; jt += kBlockKeys) {
+        load_block(A, rk, rv, voffset, row_stride, jt);
+        compute_block<R, true>(st, A, q, prm.scale_log2, jt + sub, lim_of);
     }
 
     // Combine the four 16-lane groups (each saw every fourth key) into one state per row.
@@ -278,20 +301,21 @@ __device__ __forceinline__ void process_segment(const DecodeParams& prm, int b, 
     // Store: group `sub` stores rows r with r % 4 == sub.
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        if (r >= n_rows || (r & 3) != sub) continue;
-        if (whole_sequence) {
+        if (r >= seg.n_rows || (r & 3) != sub) continue;
+        if (seg.whole) {
+            const long orow = row_index(r);
             const float inv = st.l[r] > 0.0f ? 1.0f / st.l[r] : 0.0f;
             uint4 w;
             w.x = pack_bf16(st.o[r][0] * inv, st.o[r][1] * inv);
             w.y = pack_bf16(st.o[r][2] * inv, st.o[r][3] * inv);
             w.z = pack_bf16(st.o[r][4] * inv, st.o[r][5] * inv);
             w.w = pack_bf16(st.o[r][6] * inv, st.o[r][7] * inv);
-            *reinterpret_cast<uint4*>(prm.out + (long)qrow[r] * kHeadDim + ds * 8) = w;
+            *reinterpret_cast<uint4*>(prm.out + orow * kHeadDim + ds * 8) = w;
             if (prm.lse && ds == 0)
-                prm.lse[qrow[r]] = st.l[r] > 0.0f ? (st.m[r] + __log2f(st.l[r])) * 0.6931471805599453f : kNegInf;
+                prm.lse[orow] = st.l[r] > 0.0f ? (st.m[r] + __log2f(st.l[r])) * kLn2 : kNegInf;
         } else {
-            const int t = (row0 + r) / G, g = (row0 + r) - t * G;
-            const long prow = (long)slot * (T * Hq) + t * Hq + kvh * G + g;
+            const int t = (seg.row0 + r) / G, g = (seg.row0 + r) - t * G;
+            const long prow = (long)seg.slot * (T * Hq) + t * Hq + seg.kvh * G + g;
             float4* po = reinterpret_cast<float4*>(prm.part_o + prow * kHeadDim + ds * 8);
             po[0] = make_float4(st.o[r][0], st.o[r][1], st.o[r][2], st.o[r][3]);
             po[1] = make_float4(st.o[r][4], st.o[r][5], st.o[r][6], st.o[r][7]);
@@ -300,12 +324,171 @@ __device__ __forceinline__ void process_segment(const DecodeParams& prm, int b, 
     }
 }
 
+// ---------------------------------------------------------------------------------- matrix path
+// Lane (kb, n) = (lane / 16, lane % 16).  Loads: lane holds 16 bytes (chunk n of 16) of key rows
+// 4*kb + i, i = 0..3, of the 16-key block.  MFMA index maps (any consistent map of the 128 columns
+// to the contraction index, and of output columns to physical columns, is allowed):
+//   S^T[key][row] = sum_c K[key][c] Q[row][c]: 16x16x32 step s, lane (kb, x) contracts chunk 4*s + kb
+//   O^T_e[x][row] += V[key][8*x + e] P[row][key]: 16x16x4 call (i, e) contracts keys 4*kb + i
+struct KvRegs {
+    u32x4_t k[4];
+    u32x4_t v[4];
+};
+
+__device__ __forceinline__ void load_regs(KvRegs& r, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
+                                          uint32_t voffset, uint32_t row_stride, int j_block) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t so = (uint32_t)(j_block + i) * row_stride;
+        r.k[i] = load_b128_nt(rk, voffset, so);
+        r.v[i] = load_b128_nt(rv, voffset, so);
+    }
+}
+
+struct MatrixState {
+    f32x4_t o[8];     // O^T tiles: o[e][j] = column 8*(4*kb + j) + e of row n
+    float m, l;       // row n: running max (all kb groups agree), this lane's share of the running sum
+};
+
+__device__ __forceinline__ void matrix_block(MatrixState& st, const KvRegs& r, const bf16x8_t (&qop)[4],
+                                             char* lds_wave, float scale_log2, int j_block, int lim, int kb,
+                                             int n) {
+    // K block -> LDS as [key][chunk ^ (key & 7)] (16-byte chunks), then back as the MFMA A operand.
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int key = 4 * kb + i;
+        *reinterpret_cast<u32x4_t*>(lds_wave + key * kRowBytes + ((n ^ (key & 7)) << 4)) = r.k[i];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    f32x4_t s = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int step = 0; step < 4; ++step) {
+        const int c = 4 * step + kb;
+        const bf16x8_t a = *reinterpret_cast<const bf16x8_t*>(lds_wave + n * kRowBytes + ((c ^ (n & 7)) << 4));
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, qop[step], s, 0, 0, 0);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    // s[i] = score of key j_block + 4*kb + i for row n
+    float p[4];
+    float mx = kNegInf;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        p[i] = (j_block + 4 * kb + i < lim) ? s[i] * scale_log2 : kNegInf;
+        mx = fmaxf(mx, p[i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m, mx);
+    const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
+    const float alpha = fast_exp2(st.m - m_use);
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        p[i] = fast_exp2(p[i] - m_use);
+        sum += p[i];
+    }
+    st.l = st.l * alpha + sum;
+    st.m = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[e] *= alpha;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float v[8];
+        v[0] = bf16_lo(r.v[i].x); v[1] = bf16_hi(r.v[i].x);
+        v[2] = bf16_lo(r.v[i].y); v[3] = bf16_hi(r.v[i].y);
+        v[4] = bf16_lo(r.v[i].z); v[5] = bf16_hi(r.v[i].z);
+        v[6] = bf16_lo(r.v[i].w); v[7] = bf16_hi(r.v[i].w);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[e], p[i], st.o[e], 0, 0, 0);
+    }
+}
+
+__device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Segment& seg, int lane,
+                                               char* lds_wave) {
+    const int kb = lane >> 4, n = lane & 15;
+    const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
+    const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
+    const uint32_t voffset = (uint32_t)(4 * kb) * row_stride + (uint32_t)seg.kvh * kRowBytes + n * 16;
+
+    // Row n of the tile <-> (token t, head kvh*G + g); rows past n_rows are zero padding.
+    const bool row_ok = n < seg.n_rows;
+    const int rr = seg.row0 + (row_ok ? n : 0);
+    const int t = rr / G, g = rr - t * G;
+    const long orow = (long)(seg.b * T + t) * Hq + seg.kvh * G + g;
+    bf16x8_t qop[4];
+#pragma unroll
+    for (int step = 0; step < 4; ++step) {
+        u32x4_t qv = {0u, 0u, 0u, 0u};
+        if (row_ok) qv = *reinterpret_cast<const u32x4_t*>(prm.q + orow * kHeadDim + (4 * step + kb) * 8);
+        qop[step] = __builtin_bit_cast(bf16x8_t, qv);
+    }
+    const int causal = seg.L - T + t + 1;
+    const int lim = causal < seg.j1 ? causal : seg.j1;
+
+    MatrixState st;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.o[e] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    st.m = kNegInf;
+    st.l = 0.0f;
+
+    const int n_blocks = (seg.j1 - seg.j0 + kBlockKeys - 1) / kBlockKeys;
+    KvRegs A, Bk;
+    int blk = 0;
+    load_regs(A, rk, rv, voffset, row_stride, seg.j0);
+    for (; blk + 2 <= n_blocks; blk += 2) {
+        load_regs(Bk, rk, rv, voffset, row_stride, seg.j0 + (blk + 1) * kBlockKeys);
+        matrix_block(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
+        if (blk + 2 < n_blocks) load_regs(A, rk, rv, voffset, row_stride, seg.j0 + (blk + 2) * kBlockKeys);
+        matrix_block(st, Bk, qop, lds_wave, prm.scale_log2, seg.j0 + (blk + 1) * kBlockKeys, lim, kb, n);
+    }
+    if (blk < n_blocks) matrix_block(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
+
+    float l = st.l;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (!row_ok) return;
+    if (seg.whole) {
+        const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint4 w;
+            w.x = pack_bf16(st.o[0][j] * inv, st.o[1][j] * inv);
+            w.y = pack_bf16(st.o[2][j] * inv, st.o[3][j] * inv);
+            w.z = pack_bf16(st.o[4][j] * inv, st.o[5][j] * inv);
+            w.w = pack_bf16(st.o[6][j] * inv, st.o[7][j] * inv);
+            *reinterpret_cast<uint4*>(prm.out + orow * kHeadDim + (4 * kb + j) * 8) = w;
+        }
+        if (prm.lse && kb == 0) prm.lse[orow] = l > 0.0f ? (st.m + __log2f(l)) * kLn2 : kNegInf;
+    } else {
+        const long prow = (long)seg.slot * (T * Hq) + t * Hq + seg.kvh * G + g;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            float4* po = reinterpret_cast<float4*>(prm.part_o + prow * kHeadDim + (4 * kb + j) * 8);
+            po[0] = make_float4(st.o[0][j], st.o[1][j], st.o[2][j], st.o[3][j]);
+            po[1] = make_float4(st.o[4][j], st.o[5][j], st.o[6][j], st.o[7][j]);
+        }
+        if (kb == 0) reinterpret_cast<float2*>(prm.part_ml)[prow] = make_float2(st.m, l);
+    }
+}
+
 // ---------------------------------------------------------------------------------- decode kernel
 // grid.x = pieces, grid.y = row tiles of R rows, grid.z = groups of up to 8 KV heads; block = 64 * heads.
-template <int R>
+// kMatrix selects the matrix path (R must be 16 then).
+template <int R, bool kMatrix>
 __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
+    __shared__ __attribute__((aligned(16))) char lds[kMatrix ? kMaxWavesPerBlock * kBlockKeys * kRowBytes : 16];
     const int lane = threadIdx.x & 63;
-    const int kvh = blockIdx.z * kMaxWavesPerBlock + (threadIdx.x >> 6);
+    const int wave = threadIdx.x >> 6;
+    const int kvh = blockIdx.z * kMaxWavesPerBlock + wave;
     if (kvh >= prm.n_kv_heads) return;
     const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, lane);
 
@@ -358,14 +541,23 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     }
 
     const int rows_total = prm.group * prm.q_len;
-    const int row0 = blockIdx.y * R;
-    const int n_rows = rows_total - row0 < R ? rows_total - row0 : R;
+    Segment seg;
+    seg.kvh = kvh;
+    seg.row0 = blockIdx.y * R;
+    seg.n_rows = rows_total - seg.row0 < R ? rows_total - seg.row0 : R;
     int remaining = s1 - s0;
     while (remaining > 0 && b < prm.batch) {
-        const int L = clamp_len(prm.kv_lens[b]);
+        const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
         if (L == 0) { ++b; continue; }
         const int n = (L - j < remaining) ? L - j : remaining;
-        process_segment<R>(prm, b, L, j, j + n, p + b, n == L, kvh, row0, n_rows, lane);
+        seg.b = b;
+        seg.L = L;
+        seg.j0 = j;
+        seg.j1 = j + n;
+        seg.slot = p + b;
+        seg.whole = (n == L);
+        if (kMatrix) matrix_segment(prm, seg, lane, lds + wave * (kBlockKeys * kRowBytes));
+        else vector_segment<R>(prm, seg, lane);
         remaining -= n;
         ++b;
         j = 0;
@@ -394,61 +586,88 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeParams prm) {
     }
     const int first = start / piece, last = (start + L - 1) / piece;
     if (first == last) return;
+    const long stride_rows = (long)T * Hq;
+    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + (long)(first + b) * stride_rows + th;
+    const float2* po = reinterpret_cast<const float2*>(prm.part_o + ((long)(first + b) * stride_rows + th) * kHeadDim) + lane;
+    const int n = last - first + 1;
     float M = kNegInf;
-    for (int s = first; s <= last; ++s) {
-        const float2 ml = reinterpret_cast<const float2*>(prm.part_ml)[(long)(s + b) * (T * Hq) + th];
-        M = fmaxf(M, ml.x);
-    }
+    for (int s = 0; s < n; ++s) M = fmaxf(M, ml[s * stride_rows].x);
     const float m_use = (M == kNegInf) ? 0.0f : M;
     float l = 0.0f, o0 = 0.0f, o1 = 0.0f;
-    for (int s = first; s <= last; ++s) {
-        const long prow = (long)(s + b) * (T * Hq) + th;
-        const float2 ml = reinterpret_cast<const float2*>(prm.part_ml)[prow];
-        const float w = fast_exp2(ml.x - m_use);
-        const float2 o = reinterpret_cast<const float2*>(prm.part_o + prow * kHeadDim)[lane];
-        l = __builtin_fmaf(ml.y, w, l);
+    int s = 0;
+    for (; s + 4 <= n; s += 4) {
+        float2 a[4], o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = ml[(s + u) * stride_rows];
+            o[u] = po[(s + u) * stride_rows * (kHeadDim / 2)];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float w = fast_exp2(a[u].x - m_use);
+            l = __builtin_fmaf(a[u].y, w, l);
+            o0 = __builtin_fmaf(o[u].x, w, o0);
+            o1 = __builtin_fmaf(o[u].y, w, o1);
+        }
+    }
+    for (; s < n; ++s) {
+        const float2 a = ml[s * stride_rows];
+        const float2 o = po[s * stride_rows * (kHeadDim / 2)];
+        const float w = fast_exp2(a.x - m_use);
+        l = __builtin_fmaf(a.y, w, l);
         o0 = __builtin_fmaf(o.x, w, o0);
         o1 = __builtin_fmaf(o.y, w, o1);
     }
     const float inv = l > 0.0f ? 1.0f / l : 0.0f;
     *outp = pack_bf16(o0 * inv, o1 * inv);
-    if (prm.lse && lane == 0) prm.lse[row] = l > 0.0f ? (M + __log2f(l)) * 0.6931471805599453f : kNegInf;
+    if (prm.lse && lane == 0) prm.lse[row] = l > 0.0f ? (M + __log2f(l)) * kLn2 : kNegInf;
 }
 
-template <int R>
+template <int R, bool kMatrix>
 hipError_t launch_decode_r(const DecodeParams& prm, dim3 grid, dim3 block, hipStream_t stream) {
-    hipLaunchKernelGGL(split_decode_kernel<R>, grid, block, 0, stream, prm);
+    hipLaunchKernelGGL((split_decode_kernel<R, kMatrix>), grid, block, 0, stream, prm);
     return hipGetLastError();
 }
 
 }  // namespace
 
-int rows_per_tile(int rows_total) {
-    static const int kSizes[] = {1, 2, 3, 4, 5, 6, 8, 12, 16};
+// Measured on MI355X: the matrix path is the faster one from 4 query rows per KV head upwards
+// (Qwen-style groups of 4, 5 and 8 at q_len 1, and every multi-token case); below that most of a
+// 16-row MFMA tile would be padding and the vector path does less work.
+bool use_matrix_path(int rows_total, int path) {
+    return path == kPathMatrix || (path == kPathAuto && rows_total >= 4);
+}
+
+int rows_per_tile(int rows_total, int path) {
+    if (use_matrix_path(rows_total, path)) return 16;
+    static const int kSizes[] = {1, 2, 3, 4, 5, 6, 8};
     for (int s : kSizes)
         if (rows_total <= s) return s;
-    return 16;
+    return 8;
 }
 
 hipError_t launch_decode(const DecodeParams& prm, hipStream_t stream, hipEvent_t* events) {
     const int rows_total = prm.group * prm.q_len;
-    const int R = rows_per_tile(rows_total);
+    const bool matrix = use_matrix_path(rows_total, prm.path);
+    const int R = rows_per_tile(rows_total, prm.path);
     const int heads_per_block = prm.n_kv_heads < kMaxWavesPerBlock ? prm.n_kv_heads : kMaxWavesPerBlock;
     dim3 grid((prm.n_pieces + 7) / 8 * 8, (rows_total + R - 1) / R,
               (prm.n_kv_heads + kMaxWavesPerBlock - 1) / kMaxWavesPerBlock);
     dim3 block(64 * heads_per_block);
     hipError_t e;
     if (events && (e = hipEventRecord(events[0], stream)) != hipSuccess) return e;
-    switch (R) {
-        case 1: e = launch_decode_r<1>(prm, grid, block, stream); break;
-        case 2: e = launch_decode_r<2>(prm, grid, block, stream); break;
-        case 3: e = launch_decode_r<3>(prm, grid, block, stream); break;
-        case 4: e = launch_decode_r<4>(prm, grid, block, stream); break;
-        case 5: e = launch_decode_r<5>(prm, grid, block, stream); break;
-        case 6: e = launch_decode_r<6>(prm, grid, block, stream); break;
-        case 8: e = launch_decode_r<8>(prm, grid, block, stream); break;
-        case 12: e = launch_decode_r<12>(prm, grid, block, stream); break;
-        default: e = launch_decode_r<16>(prm, grid, block, stream); break;
+    if (matrix) {
+        e = launch_decode_r<16, true>(prm, grid, block, stream);
+    } else {
+        switch (R) {
+            case 1: e = launch_decode_r<1, false>(prm, grid, block, stream); break;
+            case 2: e = launch_decode_r<2, false>(prm, grid, block, stream); break;
+            case 3: e = launch_decode_r<3, false>(prm, grid, block, stream); break;
+            case 4: e = launch_decode_r<4, false>(prm, grid, block, stream); break;
+            case 5: e = launch_decode_r<5, false>(prm, grid, block, stream); break;
+            case 6: e = launch_decode_r<6, false>(prm, grid, block, stream); break;
+            default: e = launch_decode_r<8, false>(prm, grid, block, stream); break;
+        }
     }
     if (e != hipSuccess) return e;
     if (events && (e = hipEventRecord(events[1], stream)) != hipSuccess) return e;

@@ -27,11 +27,13 @@ def _rand_case(seed, lens, T, Hq, Hkv, extra_rows=0):
 @pytest.fixture(autouse=True)
 def _default_partition():
     import paper_2510_14686_amd as xa
-    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
-    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    def reset():
+        xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+        xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+        xa.xattn_configure(xa.XATTN_CFG_PATH, 0)
+    reset()
     yield
-    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
-    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    reset()
 
 
 def test_tiny_config():
@@ -42,24 +44,34 @@ def test_tiny_config():
     check_against_oracle(w.make_q(), ks, vs, w.kv_lens(), w.scale, what="tiny")
 
 
+PATHS = {"auto": 0, "vector": 1, "matrix": 2}
+
+
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
 @pytest.mark.parametrize("name,batch,div", [("qwen3_8b_decode", 12, 4), ("long_context", 3, 16),
                                             ("spec_verify", 10, 8), ("skewed_xtensor", 40, 4)])
-def test_scaled_down_configs(name, batch, div):
-    """The four large workloads with fewer sequences and shorter lengths, every element checked.
-    Lengths still span many 16-key blocks, several pieces and ragged tails."""
+def test_scaled_down_configs(name, batch, div, path):
+    """The four large workloads with fewer sequences and shorter lengths, every element checked,
+    with the automatic inner loop and with each of the two forced.  Lengths still span many 16-key
+    blocks, several pieces and ragged tails."""
+    import paper_2510_14686_amd as xa
     from gpu_util import check_against_oracle
+    xa.xattn_configure(xa.XATTN_CFG_PATH, PATHS[path])
     w = CONFIGS[name].scaled(name + "_small", batch, div)
     lens = w.kv_lens()
     ks, vs = w.make_kv(lens)
     check_against_oracle(w.make_q(), ks, vs, lens, w.scale, what=w.name, xtensor=w.xtensor, seed=w.seed)
 
 
+@pytest.mark.parametrize("path", ["auto", "vector", "matrix"])
 @pytest.mark.parametrize("T", [1, 2, 3, 4])
 @pytest.mark.parametrize("Hq,Hkv", [(8, 2), (4, 4), (5, 1), (7, 1), (16, 2), (12, 2), (6, 2), (32, 16)])
-def test_head_and_token_shapes(T, Hq, Hkv):
+def test_head_and_token_shapes(T, Hq, Hkv, path):
     """GQA groups 1..8, 1..16 KV heads (more than 8 spills into a second workgroup set), 1..4 new
     tokens with the causal mask; rows = group * T runs from 1 to 32 (above 16: two row tiles)."""
+    import paper_2510_14686_amd as xa
     from gpu_util import check_against_oracle
+    xa.xattn_configure(xa.XATTN_CFG_PATH, PATHS[path])
     lens = [T, T + 1, 15 + T, 16 + T, 17 + T, 63, 64, 65, 200, 333]
     q, ks, vs = _rand_case(100 + T, lens, T, Hq, Hkv)
     check_against_oracle(q, ks, vs, lens, SCALE, what="T=%d Hq=%d Hkv=%d" % (T, Hq, Hkv))
@@ -90,8 +102,9 @@ def test_rows_past_kv_len_are_not_read():
     assert_parity(out_bits, lse, ref_out, ref_lse, what="padded buffers")
 
 
+@pytest.mark.parametrize("path", ["vector", "matrix"])
 @pytest.mark.parametrize("pieces,min_piece", [(8, 16), (64, 16), (1024, 16), (4096, 16), (1, 0), (37, 48)])
-def test_result_does_not_depend_on_the_partition(pieces, min_piece):
+def test_result_does_not_depend_on_the_partition(pieces, min_piece, path):
     """Any cut of the key stream into pieces gives the same result up to fp32 re-association
     (section 4.4.3: splitting a long sequence over compute units is exact)."""
     import paper_2510_14686_amd as xa
@@ -101,8 +114,9 @@ def test_result_does_not_depend_on_the_partition(pieces, min_piece):
     ref_out, ref_lse = oracle.attn(q, ks, vs, lens, SCALE)
     xa.xattn_configure(xa.XATTN_CFG_PIECES, pieces)
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, min_piece)
+    xa.xattn_configure(xa.XATTN_CFG_PATH, PATHS[path])
     out_bits, lse = gpu_attn(q, ks, vs, lens, SCALE)
-    assert_parity(out_bits, lse, ref_out, ref_lse, what="pieces=%d" % pieces)
+    assert_parity(out_bits, lse, ref_out, ref_lse, what="pieces=%d %s" % (pieces, path))
 
 
 def test_xtensor_and_plain_allocations_give_identical_bits():
