@@ -152,6 +152,9 @@ def main():
     ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
     ap.add_argument("--min-piece-tokens", type=int, default=0, help="override the minimum piece size (0 = default)")
     ap.add_argument("--path", type=int, default=0, help="inner loop: 0 automatic, 1 vector, 2 matrix cores")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
+                         "the known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     ap.add_argument("--check-sequences", type=int, default=None, help="sequences verified against the oracle (default all)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -168,6 +171,15 @@ def main():
         sys.exit(1)
     if not os.path.exists(xbuild.LIB_PATH):
         xbuild.build()
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"launches": 10, "bytes_read_per_launch": 1 << 30,
+                                             "bytes_written_per_launch": 1 << 30}}))
+        return
 
     import paper_2510_14686_amd as xa
     xa.xattn_configure(xa.XATTN_CFG_PIECES, args.pieces)

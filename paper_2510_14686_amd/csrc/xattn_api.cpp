@@ -68,7 +68,7 @@ WorkspaceLayout layout_for(int batch, int q_len, int n_q_heads, int n_pieces) {
     const size_t rows = (size_t)q_len * (size_t)n_q_heads;
     WorkspaceLayout w;
     w.meta_off = 0;
-    w.ml_off = align_up((size_t)(kMetaCum + batch) * sizeof(int32_t), 256);
+    w.ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
     w.o_off = w.ml_off + align_up(slots * rows * 2 * sizeof(float), 256);
     w.total = w.o_off + align_up(slots * rows * kHeadDim * sizeof(float), 256);
     return w;

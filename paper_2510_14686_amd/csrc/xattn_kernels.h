@@ -10,11 +10,8 @@ namespace xattn {
 constexpr int kHeadDim = 128;
 constexpr int kMaxWavesPerBlock = 8;   // one wave per KV head, up to 8 KV heads per workgroup
 
-// Workspace header (int32 words): total tokens, tokens per piece, then the exclusive prefix sums of
-// the clamped kv_lens.
-constexpr int kMetaTotal = 0;
-constexpr int kMetaPiece = 1;
-constexpr int kMetaCum = 2;
+// Workspace header: per sequence two int32 words, (first partial slot, number of segments), written
+// by the decode kernel for the merge kernel.  0 segments = no keys; 1 = finished by the decode kernel.
 
 struct DecodeParams {
     const uint16_t* q;               // bf16 [batch, q_len, n_q_heads, 128]
@@ -27,7 +24,7 @@ struct DecodeParams {
     float* lse;                      // fp32 [batch, q_len, n_q_heads] or null
     float* part_o;                   // fp32 [slots, q_len * n_q_heads, 128]
     float* part_ml;                  // fp32 [slots, q_len * n_q_heads, 2]  (max, sum)
-    int32_t* meta;                   // int32 [2 + batch]
+    int32_t* meta;                   // int32 [batch, 2]
     int n_pieces;                    // pieces the token stream is cut into (upper bound on active ones)
     int min_piece_tokens;
     int path;                        // kPathAuto, kPathVector or kPathMatrix

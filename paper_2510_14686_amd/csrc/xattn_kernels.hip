@@ -7,7 +7,10 @@
 // KV head w, so a workgroup streams one contiguous byte range of K and one of V (no block table:
 // section 4.3, "Operator Adaptation").  Each (piece, sequence) intersection is a segment.  A segment
 // that covers its whole sequence writes the final result; any other writes an un-normalised partial
-// (o, m, l) to slot piece + sequence_index, and the merge kernel combines a sequence's slots.
+// (o, m, l) to slot piece + sequence_index, and the merge kernel combines a sequence's slots (the
+// aggregation step of section 4.4.3, "Layer 2").  Combining inside the decode kernel by the last wave
+// to finish a sequence was tried and is slower: that wave alone reads all of a long sequence's
+// partials with dependent device-scope loads, while the merge kernel spreads them over the chip.
 //
 // Loads: 16 lanes hold one 256-byte K (or V) row, 8 bf16 each, one 128-bit non-temporal buffer load
 // per lane, so a wave load covers four rows; the buffer descriptor's size is the sequence's byte
@@ -500,18 +503,18 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     const bool active = (bid >> 3) < per_xcd && p < pl.n_active;
 
     if (bid == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64) {
-        // Exclusive prefix sums of the clamped lengths for the merge kernel.
+        // For the merge kernel: first partial slot and number of segments of every sequence.
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
             const int i = base + lane;
             const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
             const int incl = wave_incl_scan_i(v, lane) + run;
-            if (i < prm.batch) prm.meta[kMetaCum + i] = incl - v;
+            if (i < prm.batch) {
+                const int first = (incl - v) / pl.piece;
+                const int n_seg = v > 0 ? (incl - 1) / pl.piece - first + 1 : 0;
+                reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
+            }
             run = __shfl(incl, 63, 64);
-        }
-        if (lane == 0) {
-            prm.meta[kMetaTotal] = pl.total;
-            prm.meta[kMetaPiece] = pl.piece;
         }
     }
     if (!active) return;
@@ -565,58 +568,53 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
 }
 
 // ---------------------------------------------------------------------------------- merge kernel
+// Aggregation of the partial results of split sequences (section 4.4.3, "Layer 2"):
+//   M = max_s m_s;  l = sum_s l_s 2^(m_s - M);  out = sum_s o_s 2^(m_s - M) / l;  lse = (M + log2 l) ln 2
 // One wave per output row (b, t, h); lane holds columns 2*lane, 2*lane+1.  Sequences with a single
 // segment were finished by the decode kernel and are skipped; sequences without keys get out = 0 and
-// lse = -inf here.
+// lse = -inf here.  All loads of a round are issued before any is used.
 __global__ __launch_bounds__(256) void merge_kernel(DecodeParams prm) {
     const int lane = threadIdx.x & 63;
-    const int T = prm.q_len, Hq = prm.n_q_heads;
+    const long stride_rows = (long)prm.q_len * prm.n_q_heads;
     const long row = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= (long)prm.batch * T * Hq) return;
-    const int b = (int)(row / (T * Hq));
-    const int th = (int)(row - (long)b * (T * Hq));
-    const int L = clamp_len(prm.kv_lens[b]);
-    const int piece = prm.meta[kMetaPiece];
-    const int start = prm.meta[kMetaCum + b];
+    if (row >= (long)prm.batch * stride_rows) return;
+    const int b = (int)(row / stride_rows);
+    const int th = (int)(row - (long)b * stride_rows);
+    const int2 fs = reinterpret_cast<const int2*>(prm.meta)[b];
+    const int n = fs.y;
+    if (n == 1) return;
     uint32_t* outp = reinterpret_cast<uint32_t*>(prm.out + row * kHeadDim) + lane;
-    if (L == 0) {
+    if (n == 0) {
         *outp = 0u;
         if (prm.lse && lane == 0) prm.lse[row] = kNegInf;
         return;
     }
-    const int first = start / piece, last = (start + L - 1) / piece;
-    if (first == last) return;
-    const long stride_rows = (long)T * Hq;
-    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + (long)(first + b) * stride_rows + th;
-    const float2* po = reinterpret_cast<const float2*>(prm.part_o + ((long)(first + b) * stride_rows + th) * kHeadDim) + lane;
-    const int n = last - first + 1;
+    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + (long)fs.x * stride_rows + th;
+    const float2* po = reinterpret_cast<const float2*>(prm.part_o + ((long)fs.x * stride_rows + th) * kHeadDim) + lane;
     float M = kNegInf;
-    for (int s = 0; s < n; ++s) M = fmaxf(M, ml[s * stride_rows].x);
+    for (int base = 0; base < n; base += 64) {
+        const int s = base + lane;
+        if (s < n) M = fmaxf(M, ml[s * stride_rows].x);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
     const float m_use = (M == kNegInf) ? 0.0f : M;
     float l = 0.0f, o0 = 0.0f, o1 = 0.0f;
-    int s = 0;
-    for (; s + 4 <= n; s += 4) {
-        float2 a[4], o[4];
+    for (int s0 = 0; s0 < n; s0 += 8) {
+        float2 a[8], o[8];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            a[u] = ml[(s + u) * stride_rows];
-            o[u] = po[(s + u) * stride_rows * (kHeadDim / 2)];
+        for (int u = 0; u < 8; ++u) {
+            const int s = s0 + u < n ? s0 + u : n - 1;      // past the end: re-read the last slot, weight 0
+            a[u] = ml[s * stride_rows];
+            o[u] = po[s * stride_rows * (kHeadDim / 2)];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float w = fast_exp2(a[u].x - m_use);
+        for (int u = 0; u < 8; ++u) {
+            const float w = s0 + u < n ? fast_exp2(a[u].x - m_use) : 0.0f;
             l = __builtin_fmaf(a[u].y, w, l);
             o0 = __builtin_fmaf(o[u].x, w, o0);
             o1 = __builtin_fmaf(o[u].y, w, o1);
         }
-    }
-    for (; s < n; ++s) {
-        const float2 a = ml[s * stride_rows];
-        const float2 o = po[s * stride_rows * (kHeadDim / 2)];
-        const float w = fast_exp2(a.x - m_use);
-        l = __builtin_fmaf(a.y, w, l);
-        o0 = __builtin_fmaf(o.x, w, o0);
-        o1 = __builtin_fmaf(o.y, w, o1);
     }
     const float inv = l > 0.0f ? 1.0f / l : 0.0f;
     *outp = pack_bf16(o0 * inv, o1 * inv);

@@ -163,3 +163,79 @@ def test_lse_may_be_null_and_kv_len_below_q_len():
     out2, none = gpu_attn(q, ks, vs, lens, SCALE, want_lse=False)
     assert none is None
     np.testing.assert_array_equal(out2, out_bits)
+
+
+def test_repeated_calls_and_caller_workspace():
+    """Calls of different shapes in a row, first on the library's workspace and then on a caller's
+    buffer (handed over dirty): no call depends on what an earlier one left in the workspace."""
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from gpu_util import check_against_oracle
+    cases = [([900, 33, 2049, 500], 1, 8, 2), ([64, 3000], 4, 16, 4), ([900, 33, 2049, 500], 1, 8, 2),
+             ([5000], 2, 10, 2)]
+    for rounds in range(2):
+        for i, (lens, T, Hq, Hkv) in enumerate(cases):
+            q, ks, vs = _rand_case(40 + i, lens, T, Hq, Hkv)
+            check_against_oracle(q, ks, vs, lens, SCALE, what="repeat %d.%d" % (rounds, i))
+    need = max(xa.xattn_workspace_bytes(len(l), T, Hq, Hkv, D) for l, T, Hq, Hkv in cases)
+    buf = torch.full((need,), 0x55, dtype=torch.uint8, device="cuda")      # dirty on purpose
+    xa.xattn_set_workspace(buf, need)
+    try:
+        for i, (lens, T, Hq, Hkv) in enumerate(cases):
+            q, ks, vs = _rand_case(40 + i, lens, T, Hq, Hkv)
+            check_against_oracle(q, ks, vs, lens, SCALE, what="caller workspace %d" % i)
+        small = torch.zeros(1 << 12, dtype=torch.uint8, device="cuda")
+        xa.xattn_set_workspace(small, 1 << 12)
+        with pytest.raises(xa.XattnError) as e:
+            q, ks, vs = _rand_case(40, cases[0][0], 1, 8, 2)
+            check_against_oracle(q, ks, vs, cases[0][0], SCALE)
+        assert e.value.status == xa.binding.XATTN_ENOMEM
+    finally:
+        torch.cuda.synchronize()
+        xa.xattn_set_workspace(None, 0)
+
+
+def test_sequences_without_keys():
+    """kv_len = 0 (a contract violation the library tolerates): out = 0 and lse = -inf for that
+    sequence, the others unaffected."""
+    from gpu_util import assert_parity, gpu_attn
+    lens = [0, 40, 0, 700]
+    q, ks, vs = _rand_case(13, [1, 40, 1, 700], 2, 8, 2)
+    lens_gpu = [0, 40, 0, 700]
+    out_bits, lse = gpu_attn(q, ks, vs, lens_gpu, SCALE)
+    assert np.all(out_bits[[0, 2]] == 0) and np.all(np.isneginf(lse[[0, 2]]))
+    ref_out, ref_lse = oracle.attn(q[[1, 3]], [ks[1], ks[3]], [vs[1], vs[3]], [40, 700], SCALE)
+    assert_parity(out_bits[[1, 3]], lse[[1, 3]], ref_out, ref_lse, what="neighbours of empty sequences")
+
+
+@pytest.mark.parametrize("path", ["vector", "matrix"])
+def test_split_sequences_are_aggregated_identically_every_time(path):
+    """Long sequences cut into many segments whose partial results cross compute units: 300 calls in
+    a row must give the same bits (the aggregation order is fixed) and match the oracle.  A stale or
+    half-written partial read by the aggregation would show up as a differing call."""
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    xa.xattn_configure(xa.XATTN_CFG_PATH, PATHS[path])
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 16)
+    lens = [9000, 300, 12000, 64, 7000]
+    T, Hq, Hkv = 1, 16, 4
+    q, ks, vs = _rand_case(50, lens, T, Hq, Hkv)
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, SCALE)
+    with xa.KVStore(ks, vs) as store:
+        qd = torch.from_numpy(q.view(np.int16)).cuda()
+        lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        outs = torch.zeros((300, len(lens), T, Hq, D), dtype=torch.int16, device="cuda")
+        lses = torch.zeros((300, len(lens), T, Hq), dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+        for i in range(300):
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, len(lens), T, Hq, Hkv, D, SCALE, outs[i], lses[i],
+                            stream)
+        torch.cuda.synchronize()
+        outs_h = outs.cpu().numpy().view(np.uint16)
+        lses_h = lses.cpu().numpy()
+    assert_parity(outs_h[0], lses_h[0], ref_out, ref_lse, what="first call")
+    for i in range(1, 300):
+        assert np.array_equal(outs_h[i], outs_h[0]) and np.array_equal(lses_h[i], lses_h[0]), "call %d differs" % i
