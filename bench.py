@@ -152,6 +152,7 @@ def main():
     ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
     ap.add_argument("--min-piece-tokens", type=int, default=0, help="override the minimum piece size (0 = default)")
     ap.add_argument("--path", type=int, default=0, help="inner loop: 0 automatic, 1 vector, 2 matrix cores")
+    ap.add_argument("--pv-mode", type=int, default=0, help="matrix path p.V product: 0 default (bf16 MFMA, hi+lo parts), 1 fp32 MFMA, 2 single bf16 MFMA")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
                          "the known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -185,6 +186,7 @@ def main():
     xa.xattn_configure(xa.XATTN_CFG_PIECES, args.pieces)
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, args.min_piece_tokens)
     xa.xattn_configure(xa.XATTN_CFG_PATH, args.path)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, args.pv_mode)
     head = workloads.CONFIGS[args.workload]
     main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True)
     others = {}

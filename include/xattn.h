@@ -100,9 +100,14 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *   XATTN_CFG_PATH              inner loop of the decode kernel: 0 = automatic (vector path below 4
  *                               query rows per KV head, i.e. group * q_len < 4; matrix-core path
  *                               from 4 up), 1 = vector path, 2 = matrix-core path (section 4.4.1)
+ *   XATTN_CFG_PV_MODE           matrix-core path, product of softmax weights and V: 0 = default, bf16
+ *                               MFMA on hi + lo bf16 parts of the weights (16 significant bits);
+ *                               1 = fp32 MFMA (weights exact, slower); 2 = one bf16 MFMA (weights
+ *                               rounded to bf16)
  * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
  */
-enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3 };
+enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3,
+       XATTN_CFG_PV_MODE = 4 };
 int xattn_configure(int key, int value);
 
 /*

@@ -50,6 +50,7 @@ int g_cfg_pieces = 0;
 int g_cfg_min_piece = 0;
 int g_cfg_timing = 0;
 int g_cfg_path = 0;
+int g_cfg_pv_mode = 0;
 
 constexpr int kMaxTimedCalls = 4096;
 std::vector<hipEvent_t> g_events;     // three per timed call, created on demand, reused across series
@@ -124,6 +125,10 @@ int xattn_configure(int key, int value) {
         case XATTN_CFG_PATH:
             if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: path %d is not 0, 1 or 2", value);
             g_cfg_path = value;
+            return XATTN_OK;
+        case XATTN_CFG_PV_MODE:
+            if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: pv mode %d is not 0, 1 or 2", value);
+            g_cfg_pv_mode = value;
             return XATTN_OK;
         default: return fail(XATTN_EINVAL, "xattn_configure: unknown key %d", key);
     }
@@ -214,6 +219,7 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     prm.path = g_cfg_path;
+    prm.pv_mode = g_cfg_pv_mode;
 
     hipEvent_t* events = nullptr;
     if (g_cfg_timing && g_timed_calls < kMaxTimedCalls) {

@@ -28,7 +28,13 @@ struct DecodeParams {
     int n_pieces;                    // pieces the token stream is cut into (upper bound on active ones)
     int min_piece_tokens;
     int path;                        // kPathAuto, kPathVector or kPathMatrix
+    int pv_mode;                     // matrix path: kPvBf16x2, kPvFp32 or kPvBf16
 };
+
+// How the matrix path multiplies the softmax weights p with V.
+constexpr int kPvBf16x2 = 0;   // default: bf16 MFMA 16x16x16 twice, p as hi + lo bf16 parts (16 significant bits)
+constexpr int kPvFp32 = 1;     // fp32 MFMA 16x16x4, p exact; 4x the matrix-core time, measurably slower
+constexpr int kPvBf16 = 2;     // bf16 MFMA 16x16x16 once, p rounded to bf16; same speed as the default, less exact
 
 // Inner-loop choice: automatic = vector path below 4 query rows per KV head, matrix path from 4 up.
 constexpr int kPathAuto = 0;

@@ -22,8 +22,9 @@
 //     online softmax in fp32 (log2 domain); p.v by fp32 FMA.
 //   * matrix path (tiles of 16 rows, the multi-token verification case): the K block is transposed
 //     through wave-private LDS into the MFMA operand layout, S^T = K Q^T by bf16 MFMA 16x16x32;
-//     softmax on the accumulator layout (a lane holds 4 keys of one row); O^T += V^T P^T by fp32 MFMA
-//     16x16x4 straight from the V registers (p stays fp32, V never touches LDS).
+//     softmax on the accumulator layout (a lane holds 4 keys of one row); O^T += V^T P^T by bf16 MFMA
+//     16x16x16 straight from the V registers (V never touches LDS), with p fed as hi + lo bf16 parts
+//     so that it keeps 16 significant bits.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -42,6 +43,9 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 
 // ---------------------------------------------------------------------------------- lane helpers
 template <int kCtrl>
@@ -353,6 +357,7 @@ struct MatrixState {
     float m, l;       // row n: running max (all kb groups agree), this lane's share of the running sum
 };
 
+template <int kPv>
 __device__ __forceinline__ void matrix_block(MatrixState& st, const KvRegs& r, const bf16x8_t (&qop)[4],
                                              char* lds_wave, float scale_log2, int j_block, int lim, int kb,
                                              int n) {
@@ -401,18 +406,49 @@ __device__ __forceinline__ void matrix_block(MatrixState& st, const KvRegs& r, c
 #pragma unroll
         for (int e = 0; e < 8; ++e) st.o[e] *= alpha;
     }
+    if (kPv == kPvFp32) {
+        // O^T_e += V_i[e] (x) p_i over the 4 key groups: fp32 MFMA, p exact.
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float v[8];
-        v[0] = bf16_lo(r.v[i].x); v[1] = bf16_hi(r.v[i].x);
-        v[2] = bf16_lo(r.v[i].y); v[3] = bf16_hi(r.v[i].y);
-        v[4] = bf16_lo(r.v[i].z); v[5] = bf16_hi(r.v[i].z);
-        v[6] = bf16_lo(r.v[i].w); v[7] = bf16_hi(r.v[i].w);
+        for (int i = 0; i < 4; ++i) {
+            float v[8];
+            v[0] = bf16_lo(r.v[i].x); v[1] = bf16_hi(r.v[i].x);
+            v[2] = bf16_lo(r.v[i].y); v[3] = bf16_hi(r.v[i].y);
+            v[4] = bf16_lo(r.v[i].z); v[5] = bf16_hi(r.v[i].z);
+            v[6] = bf16_lo(r.v[i].w); v[7] = bf16_hi(r.v[i].w);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) st.o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[e], p[i], st.o[e], 0, 0, 0);
+            for (int e = 0; e < 8; ++e) st.o[e] = __builtin_amdgcn_mfma_f32_16x16x4f32(v[e], p[i], st.o[e], 0, 0, 0);
+        }
+    } else {
+        // bf16 MFMA 16x16x16 contracts the block's 16 keys at once: lane (kb, x) supplies keys 4*kb + i,
+        // i = 0..3, of column 8*x + e (the e-th bf16 of its four V registers) and of row n (its four p).
+        // kPvBf16x2 feeds p as hi + lo bf16 parts in two MFMAs, which keeps p to 16 significant bits.
+        const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
+        const bf16x2_t h01 = __builtin_convertvector(p01, bf16x2_t), h23 = __builtin_convertvector(p23, bf16x2_t);
+        const u32x2_t ph = {__builtin_bit_cast(uint32_t, h01), __builtin_bit_cast(uint32_t, h23)};
+        u32x2_t pl = {0u, 0u};
+        if (kPv == kPvBf16x2) {
+            const f32x2_t r01 = p01 - __builtin_convertvector(h01, f32x2_t);
+            const f32x2_t r23 = p23 - __builtin_convertvector(h23, f32x2_t);
+            pl.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(r01, bf16x2_t));
+            pl.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(r23, bf16x2_t));
+        }
+        const uint32_t vw[4][4] = {{r.v[0].x, r.v[0].y, r.v[0].z, r.v[0].w}, {r.v[1].x, r.v[1].y, r.v[1].z, r.v[1].w},
+                                   {r.v[2].x, r.v[2].y, r.v[2].z, r.v[2].w}, {r.v[3].x, r.v[3].y, r.v[3].z, r.v[3].w}};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;      // high or low halves of both words
+            const u32x2_t a = {__builtin_amdgcn_perm(vw[1][e >> 1], vw[0][e >> 1], sel),
+                               __builtin_amdgcn_perm(vw[3][e >> 1], vw[2][e >> 1], sel)};
+            st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a),
+                                                                __builtin_bit_cast(s16x4_t, ph), st.o[e], 0, 0, 0);
+            if (kPv == kPvBf16x2)
+                st.o[e] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4_t, a),
+                                                                    __builtin_bit_cast(s16x4_t, pl), st.o[e], 0, 0, 0);
+        }
     }
 }
 
+template <int kPv>
 __device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Segment& seg, int lane,
                                                char* lds_wave) {
     const int kb = lane >> 4, n = lane & 15;
@@ -449,11 +485,11 @@ __device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Se
     load_regs(A, rk, rv, voffset, row_stride, seg.j0);
     for (; blk + 2 <= n_blocks; blk += 2) {
         load_regs(Bk, rk, rv, voffset, row_stride, seg.j0 + (blk + 1) * kBlockKeys);
-        matrix_block(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
+        matrix_block<kPv>(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
         if (blk + 2 < n_blocks) load_regs(A, rk, rv, voffset, row_stride, seg.j0 + (blk + 2) * kBlockKeys);
-        matrix_block(st, Bk, qop, lds_wave, prm.scale_log2, seg.j0 + (blk + 1) * kBlockKeys, lim, kb, n);
+        matrix_block<kPv>(st, Bk, qop, lds_wave, prm.scale_log2, seg.j0 + (blk + 1) * kBlockKeys, lim, kb, n);
     }
-    if (blk < n_blocks) matrix_block(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
+    if (blk < n_blocks) matrix_block<kPv>(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
 
     float l = st.l;
     l += __shfl_xor(l, 16, 64);
@@ -486,7 +522,7 @@ __device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Se
 // ---------------------------------------------------------------------------------- decode kernel
 // grid.x = pieces, grid.y = row tiles of R rows, grid.z = groups of up to 8 KV heads; block = 64 * heads.
 // kMatrix selects the matrix path (R must be 16 then).
-template <int R, bool kMatrix>
+template <int R, bool kMatrix, int kPv>
 __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     __shared__ __attribute__((aligned(16))) char lds[kMatrix ? kMaxWavesPerBlock * kBlockKeys * kRowBytes : 16];
     const int lane = threadIdx.x & 63;
@@ -559,7 +595,7 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
         seg.j1 = j + n;
         seg.slot = p + b;
         seg.whole = (n == L);
-        if (kMatrix) matrix_segment(prm, seg, lane, lds + wave * (kBlockKeys * kRowBytes));
+        if (kMatrix) matrix_segment<kPv>(prm, seg, lane, lds + wave * (kBlockKeys * kRowBytes));
         else vector_segment<R>(prm, seg, lane);
         remaining -= n;
         ++b;
@@ -621,9 +657,9 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeParams prm) {
     if (prm.lse && lane == 0) prm.lse[row] = l > 0.0f ? (M + __log2f(l)) * kLn2 : kNegInf;
 }
 
-template <int R, bool kMatrix>
+template <int R, bool kMatrix, int kPv = kPvBf16x2>
 hipError_t launch_decode_r(const DecodeParams& prm, dim3 grid, dim3 block, hipStream_t stream) {
-    hipLaunchKernelGGL((split_decode_kernel<R, kMatrix>), grid, block, 0, stream, prm);
+    hipLaunchKernelGGL((split_decode_kernel<R, kMatrix, kPv>), grid, block, 0, stream, prm);
     return hipGetLastError();
 }
 
@@ -655,7 +691,11 @@ hipError_t launch_decode(const DecodeParams& prm, hipStream_t stream, hipEvent_t
     hipError_t e;
     if (events && (e = hipEventRecord(events[0], stream)) != hipSuccess) return e;
     if (matrix) {
-        e = launch_decode_r<16, true>(prm, grid, block, stream);
+        switch (prm.pv_mode) {
+            case kPvBf16: e = launch_decode_r<16, true, kPvBf16>(prm, grid, block, stream); break;
+            case kPvFp32: e = launch_decode_r<16, true, kPvFp32>(prm, grid, block, stream); break;
+            default: e = launch_decode_r<16, true, kPvBf16x2>(prm, grid, block, stream); break;
+        }
     } else {
         switch (R) {
             case 1: e = launch_decode_r<1, false>(prm, grid, block, stream); break;

@@ -31,6 +31,7 @@ def _default_partition():
         xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
         xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
         xa.xattn_configure(xa.XATTN_CFG_PATH, 0)
+        xa.xattn_configure(xa.XATTN_CFG_PV_MODE, 0)
     reset()
     yield
     reset()
@@ -239,3 +240,18 @@ def test_split_sequences_are_aggregated_identically_every_time(path):
     assert_parity(outs_h[0], lses_h[0], ref_out, ref_lse, what="first call")
     for i in range(1, 300):
         assert np.array_equal(outs_h[i], outs_h[0]) and np.array_equal(lses_h[i], lses_h[0]), "call %d differs" % i
+
+
+@pytest.mark.parametrize("pv_mode", [0, 1, 2])
+def test_matrix_path_pv_modes(pv_mode):
+    """The three ways the matrix path multiplies softmax weights with V all meet the parity bar;
+    the default (hi + lo bf16 parts) and fp32 agree with the oracle as closely as bf16 output allows."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import check_against_oracle
+    xa.xattn_configure(xa.XATTN_CFG_PATH, PATHS["matrix"])
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, pv_mode)
+    lens = [700, 33, 4, 2049, 16, 512, 90, 5000]
+    q, ks, vs = _rand_case(60, lens, 4, 16, 4)
+    (max_abs, rel_rows, rel_all, lse_err), _, _ = check_against_oracle(q, ks, vs, lens, SCALE, what="pv %d" % pv_mode)
+    if pv_mode in (0, 1):
+        assert rel_all < 1.9e-3        # bf16 rounding of the output alone gives about 1.66e-3
