@@ -30,7 +30,13 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per decode-kernel launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script (summaries under profiles/), scaled by the factor a plain copy kernel of known size gives.
 # None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/split_decode_kernel__<workload>.txt: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 of the decode kernel
+    "qwen3_8b_decode": 646474913,
+    "long_context": 1628692004,
+    "spec_verify": 2460047248,
+    "skewed_xtensor": 2154813306,
+}
 
 
 def log(*a):
