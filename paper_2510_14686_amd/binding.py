@@ -37,8 +37,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or _build.LIB_PATH
+    p = path or os.environ.get("XATTN_LIBRARY") or _build.LIB_PATH      # XATTN_LIBRARY: another build of libxattn.so
     if not os.path.exists(p):
+        if p != _build.LIB_PATH:
+            raise FileNotFoundError(p)
         p = _build.build()
     lib = ctypes.CDLL(p)
     vp, i32, sz, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint64

@@ -36,6 +36,9 @@ namespace {
 constexpr int kU = 4;                 // key rows per 16-lane group per block
 constexpr int kBlockKeys = 4 * kU;    // key rows per wave per block
 constexpr int kRowBytes = kHeadDim * 2;
+// Wave-private LDS of the matrix path: a 16-key K block (4 KiB) during the key loop, a 16-row fp32
+// output tile with padded rows (16 x 528 bytes) when a segment is stored.
+constexpr int kLdsPerWave = 16 * (kHeadDim * 4 + 16);
 constexpr float kNegInf = -__builtin_inff();
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -97,6 +100,18 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, ui
 // 128-bit non-temporal load at base + voffset (per lane) + soffset (wave-uniform).
 __device__ __forceinline__ u32x4_t load_b128_nt(__amdgpu_buffer_rsrc_t rsrc, uint32_t voffset, uint32_t soffset) {
     return __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset, (int)soffset, 2 /* nt */);
+}
+
+// Stores of results and partial results: whole rows per instruction (see matrix_finish).  A segment
+// that is followed by another one in the same workgroup is written through (sc1): left to the L2's
+// write-back policy, its dirty lines are evicted one by one into the saturated read stream later
+// (measured on the 16-row workload: 25 MB of partial results cost 37 us of a 400 us kernel, written
+// through as full lines 14 us).  A workgroup's last segment keeps the write-back policy: its stores
+// complete at the L2 and are flushed in bulk when the kernel ends, which is faster than waiting for
+// a write-through at the kernel's tail.
+template <bool kWriteThrough>
+__device__ __forceinline__ void store_b128(void* base, uint32_t bytes, uint32_t off, u32x4_t v) {
+    __builtin_amdgcn_raw_buffer_store_b128(v, make_rsrc(base, bytes), (int)off, 0, kWriteThrough ? 16 /* sc1 */ : 0);
 }
 
 // ---------------------------------------------------------------------------------- the plan
@@ -448,54 +463,99 @@ __device__ __forceinline__ void matrix_block(MatrixState& st, const KvRegs& r, c
     }
 }
 
-template <int kPv>
-__device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Segment& seg, int lane,
-                                               char* lds_wave) {
+// A segment in flight on the matrix path: its per-lane constants, its Q operand and the loads of its
+// first block.  matrix_begin issues the loads, matrix_run consumes the blocks, matrix_finish stores.
+// The kernel begins the next segment before it finishes the current one, so that the new
+// segment's first loads are not queued behind the old segment's stores (a wave's memory operations
+// complete in order, and a store's completion takes several microseconds under a saturated read
+// stream) and the read stream does not drain at a segment boundary.
+struct MatrixCtx {
+    Segment seg;
+    __amdgpu_buffer_rsrc_t rk, rv;
+    uint32_t voffset;
+    bf16x8_t qop[4];
+    int lim;          // first key index row n may not see
+    bool row_ok;      // row n of the tile exists
+    int t, g;         // row n <-> (token, head within the group)
+    long orow;        // output row of row n
+    KvRegs first;     // block 0
+};
+
+__device__ __forceinline__ void matrix_begin(MatrixCtx& c, const DecodeParams& prm, const Segment& seg, int lane) {
     const int kb = lane >> 4, n = lane & 15;
     const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
     const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
-    const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
-    const uint32_t voffset = (uint32_t)(4 * kb) * row_stride + (uint32_t)seg.kvh * kRowBytes + n * 16;
-
+    c.seg = seg;
+    c.rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
+    c.rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
+    c.voffset = (uint32_t)(4 * kb) * row_stride + (uint32_t)seg.kvh * kRowBytes + n * 16;
+    load_regs(c.first, c.rk, c.rv, c.voffset, row_stride, seg.j0);
     // Row n of the tile <-> (token t, head kvh*G + g); rows past n_rows are zero padding.
-    const bool row_ok = n < seg.n_rows;
-    const int rr = seg.row0 + (row_ok ? n : 0);
-    const int t = rr / G, g = rr - t * G;
-    const long orow = (long)(seg.b * T + t) * Hq + seg.kvh * G + g;
-    bf16x8_t qop[4];
+    c.row_ok = n < seg.n_rows;
+    const int rr = seg.row0 + (c.row_ok ? n : 0);
+    c.t = rr / G;
+    c.g = rr - c.t * G;
+    c.orow = (long)(seg.b * T + c.t) * Hq + seg.kvh * G + c.g;
 #pragma unroll
     for (int step = 0; step < 4; ++step) {
         u32x4_t qv = {0u, 0u, 0u, 0u};
-        if (row_ok) qv = *reinterpret_cast<const u32x4_t*>(prm.q + orow * kHeadDim + (4 * step + kb) * 8);
-        qop[step] = __builtin_bit_cast(bf16x8_t, qv);
+        if (c.row_ok) qv = *reinterpret_cast<const u32x4_t*>(prm.q + c.orow * kHeadDim + (4 * step + kb) * 8);
+        c.qop[step] = __builtin_bit_cast(bf16x8_t, qv);
     }
-    const int causal = seg.L - T + t + 1;
-    const int lim = causal < seg.j1 ? causal : seg.j1;
+    const int causal = seg.L - T + c.t + 1;
+    c.lim = causal < seg.j1 ? causal : seg.j1;
+}
 
-    MatrixState st;
+template <int kPv>
+__device__ __forceinline__ void matrix_run(MatrixState& st, MatrixCtx& c, const DecodeParams& prm, int lane,
+                                           char* lds_wave) {
+    const int kb = lane >> 4, n = lane & 15;
+    const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
+    const Segment& seg = c.seg;
 #pragma unroll
     for (int e = 0; e < 8; ++e) st.o[e] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
     st.m = kNegInf;
     st.l = 0.0f;
-
+    // Two register buffers: the next block's 8 loads per lane are issued before the current block's
+    // arithmetic.
     const int n_blocks = (seg.j1 - seg.j0 + kBlockKeys - 1) / kBlockKeys;
-    KvRegs A, Bk;
+    auto key0 = [&](int blk) { return seg.j0 + blk * kBlockKeys; };
+    KvRegs Bk;
     int blk = 0;
-    load_regs(A, rk, rv, voffset, row_stride, seg.j0);
     for (; blk + 2 <= n_blocks; blk += 2) {
-        load_regs(Bk, rk, rv, voffset, row_stride, seg.j0 + (blk + 1) * kBlockKeys);
-        matrix_block<kPv>(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
-        if (blk + 2 < n_blocks) load_regs(A, rk, rv, voffset, row_stride, seg.j0 + (blk + 2) * kBlockKeys);
-        matrix_block<kPv>(st, Bk, qop, lds_wave, prm.scale_log2, seg.j0 + (blk + 1) * kBlockKeys, lim, kb, n);
+        load_regs(Bk, c.rk, c.rv, c.voffset, row_stride, key0(blk + 1));
+        matrix_block<kPv>(st, c.first, c.qop, lds_wave, prm.scale_log2, key0(blk), c.lim, kb, n);
+        if (blk + 2 < n_blocks) load_regs(c.first, c.rk, c.rv, c.voffset, row_stride, key0(blk + 2));
+        matrix_block<kPv>(st, Bk, c.qop, lds_wave, prm.scale_log2, key0(blk + 1), c.lim, kb, n);
     }
-    if (blk < n_blocks) matrix_block<kPv>(st, A, qop, lds_wave, prm.scale_log2, seg.j0 + blk * kBlockKeys, lim, kb, n);
+    if (blk < n_blocks) matrix_block<kPv>(st, c.first, c.qop, lds_wave, prm.scale_log2, key0(blk), c.lim, kb, n);
+}
 
+template <bool kWriteThrough>
+__device__ __forceinline__ void matrix_finish(const MatrixState& st, const MatrixCtx& c, const DecodeParams& prm,
+                                              int lane, char* lds_wave) {
+    const int kb = lane >> 4, n = lane & 15;
+    const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
+    const Segment& seg = c.seg;
     float l = st.l;
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    if (!row_ok) return;
+    // Store through LDS so that every store instruction writes whole contiguous rows (a lane's own
+    // accumulators are 16-byte pieces of 16 different rows).
+    auto fence = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    auto row_of = [&](int r, long* out_row, int* seq_row) {      // tile row r -> output row, row within the sequence
+        const int rr2 = seg.row0 + r;
+        const int t2 = rr2 / G, g2 = rr2 - t2 * G;
+        *seq_row = t2 * Hq + seg.kvh * G + g2;
+        *out_row = (long)seg.b * T * Hq + *seq_row;
+    };
+    fence();      // the last block's LDS reads are done
     if (seg.whole) {
+        constexpr int kPitch = kRowBytes + 16;                   // bf16 rows, padded against bank conflicts
         const float inv = l > 0.0f ? 1.0f / l : 0.0f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -504,19 +564,49 @@ __device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Se
             w.y = pack_bf16(st.o[2][j] * inv, st.o[3][j] * inv);
             w.z = pack_bf16(st.o[4][j] * inv, st.o[5][j] * inv);
             w.w = pack_bf16(st.o[6][j] * inv, st.o[7][j] * inv);
-            *reinterpret_cast<uint4*>(prm.out + orow * kHeadDim + (4 * kb + j) * 8) = w;
+            *reinterpret_cast<uint4*>(lds_wave + n * kPitch + (4 * kb + j) * 16) = w;
         }
-        if (prm.lse && kb == 0) prm.lse[orow] = l > 0.0f ? (st.m + __log2f(l)) * kLn2 : kNegInf;
+        fence();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                             // 4 rows of 256 bytes per store instruction
+            const int r = 4 * i + (lane >> 4);
+            if (r < seg.n_rows) {
+                long orow2;
+                int th2;
+                row_of(r, &orow2, &th2);
+                const u32x4_t w = *reinterpret_cast<const u32x4_t*>(lds_wave + r * kPitch + (lane & 15) * 16);
+                store_b128<kWriteThrough>(prm.out + (long)seg.b * T * Hq * kHeadDim, (uint32_t)(T * Hq * kRowBytes),
+                              (uint32_t)(th2 * kRowBytes + (lane & 15) * 16), w);
+            }
+        }
+        if (c.row_ok && prm.lse && kb == 0) prm.lse[c.orow] = l > 0.0f ? (st.m + __log2f(l)) * kLn2 : kNegInf;
     } else {
-        const long prow = (long)seg.slot * (T * Hq) + t * Hq + seg.kvh * G + g;
+        constexpr int kPitch = kHeadDim * 4 + 16;                // fp32 rows, padded
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            float4* po = reinterpret_cast<float4*>(prm.part_o + prow * kHeadDim + (4 * kb + j) * 8);
-            po[0] = make_float4(st.o[0][j], st.o[1][j], st.o[2][j], st.o[3][j]);
-            po[1] = make_float4(st.o[4][j], st.o[5][j], st.o[6][j], st.o[7][j]);
+            float4* w = reinterpret_cast<float4*>(lds_wave + n * kPitch + (4 * kb + j) * 32);
+            w[0] = make_float4(st.o[0][j], st.o[1][j], st.o[2][j], st.o[3][j]);
+            w[1] = make_float4(st.o[4][j], st.o[5][j], st.o[6][j], st.o[7][j]);
         }
-        if (kb == 0) reinterpret_cast<float2*>(prm.part_ml)[prow] = make_float2(st.m, l);
+        fence();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {                             // 2 rows of 512 bytes per store instruction
+            const int r = 2 * i + (lane >> 5);
+            if (r < seg.n_rows) {
+                long orow2;
+                int th2;
+                row_of(r, &orow2, &th2);
+                const u32x4_t w = *reinterpret_cast<const u32x4_t*>(lds_wave + r * kPitch + (lane & 31) * 16);
+                store_b128<kWriteThrough>(prm.part_o + (long)seg.slot * (T * Hq) * kHeadDim, (uint32_t)(T * Hq * kHeadDim * 4),
+                              (uint32_t)(th2 * kHeadDim * 4 + (lane & 31) * 16), w);
+            }
+        }
+        if (c.row_ok && kb == 0) {
+            const long prow = (long)seg.slot * (T * Hq) + c.t * Hq + seg.kvh * G + c.g;
+            reinterpret_cast<float2*>(prm.part_ml)[prow] = make_float2(st.m, l);
+        }
     }
+    fence();      // the next segment's K blocks reuse this LDS
 }
 
 // ---------------------------------------------------------------------------------- decode kernel
@@ -524,7 +614,7 @@ __device__ __forceinline__ void matrix_segment(const DecodeParams& prm, const Se
 // kMatrix selects the matrix path (R must be 16 then).
 template <int R, bool kMatrix, int kPv>
 __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
-    __shared__ __attribute__((aligned(16))) char lds[kMatrix ? kMaxWavesPerBlock * kBlockKeys * kRowBytes : 16];
+    __shared__ __attribute__((aligned(16))) char lds[kMatrix ? kMaxWavesPerBlock * kLdsPerWave : 16];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int kvh = blockIdx.z * kMaxWavesPerBlock + wave;
@@ -585,21 +675,47 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     seg.row0 = blockIdx.y * R;
     seg.n_rows = rows_total - seg.row0 < R ? rows_total - seg.row0 : R;
     int remaining = s1 - s0;
-    while (remaining > 0 && b < prm.batch) {
-        const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
-        if (L == 0) { ++b; continue; }
-        const int n = (L - j < remaining) ? L - j : remaining;
-        seg.b = b;
-        seg.L = L;
-        seg.j0 = j;
-        seg.j1 = j + n;
-        seg.slot = p + b;
-        seg.whole = (n == L);
-        if (kMatrix) matrix_segment<kPv>(prm, seg, lane, lds + wave * (kBlockKeys * kRowBytes));
-        else vector_segment<R>(prm, seg, lane);
-        remaining -= n;
-        ++b;
-        j = 0;
+    // Next (piece, sequence) intersection of this piece, in stream order; false when the piece is done.
+    auto next_segment = [&](Segment& out) {
+        while (remaining > 0 && b < prm.batch) {
+            const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
+            if (L == 0) { ++b; continue; }
+            const int n = (L - j < remaining) ? L - j : remaining;
+            out = seg;
+            out.b = b;
+            out.L = L;
+            out.j0 = j;
+            out.j1 = j + n;
+            out.slot = p + b;
+            out.whole = (n == L);
+            remaining -= n;
+            ++b;
+            j = 0;
+            return true;
+        }
+        return false;
+    };
+    if (kMatrix) {
+        char* lds_wave = lds + wave * kLdsPerWave;
+        Segment cur_seg;
+        if (!next_segment(cur_seg)) return;
+        MatrixCtx cur;
+        matrix_begin(cur, prm, cur_seg, lane);
+        for (;;) {
+            MatrixState st;
+            matrix_run<kPv>(st, cur, prm, lane, lds_wave);
+            Segment nxt_seg;
+            const bool more = next_segment(nxt_seg);
+            MatrixCtx nxt;
+            if (more) matrix_begin(nxt, prm, nxt_seg, lane);     // its loads go out before cur's stores
+            if (more) matrix_finish<true>(st, cur, prm, lane, lds_wave);
+            else matrix_finish<false>(st, cur, prm, lane, lds_wave);
+            if (!more) break;
+            cur = nxt;
+        }
+    } else {
+        Segment s2;
+        while (next_segment(s2)) vector_segment<R>(prm, s2, lane);
     }
 }
 
