@@ -95,7 +95,8 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  * result does not depend on the partition.  key:
  *   XATTN_CFG_PIECES            number of equal-token pieces the batch's keys are cut into
  *                               (= workgroups launched); 0 = automatic (the CU count)
- *   XATTN_CFG_MIN_PIECE_TOKENS  lower bound on a piece's tokens; 0 = default (64)
+ *   XATTN_CFG_MIN_PIECE_TOKENS  lower bound on a piece's tokens; 0 = default (64); values below 16
+ *                               count as 16
  *   XATTN_CFG_TIMING            1 = record per-kernel events (see xattn_timing_read); 0 = off
  *   XATTN_CFG_PATH              inner loop of the decode kernel: 0 = automatic (vector path below 4
  *                               query rows per KV head, i.e. group * q_len < 4; matrix-core path

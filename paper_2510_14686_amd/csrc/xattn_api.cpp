@@ -218,6 +218,7 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
     prm.part_o = reinterpret_cast<float*>(ws + w.o_off);
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
+    if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;      // one 16-key block at least
     prm.path = g_cfg_path;
     prm.pv_mode = g_cfg_pv_mode;
 

@@ -2,8 +2,8 @@
 //
 // Work decomposition (paper section 4.4.3, "Layer 3": balance compute units by token count, split
 // long sequences, let short ones share a unit).  The keys of the whole batch form one stream of
-// N = sum_b kv_lens[b] tokens, cut into equal pieces of C tokens; workgroup p owns tokens
-// [p*C, (p+1)*C) of that stream, whatever sequences they belong to.  Inside a workgroup wave w owns
+// N = sum_b kv_lens[b] tokens, cut into P pieces of N / P tokens (to within one 16-key block);
+// workgroup p owns one piece of that stream, whatever sequences it falls in.  Inside a workgroup wave w owns
 // KV head w, so a workgroup streams one contiguous byte range of K and one of V (no block table:
 // section 4.3, "Operator Adaptation").  Each (piece, sequence) intersection is a segment.  A segment
 // that covers its whole sequence writes the final result; any other writes an un-normalised partial
@@ -117,8 +117,7 @@ __device__ __forceinline__ void store_b128(void* base, uint32_t bytes, uint32_t 
 // ---------------------------------------------------------------------------------- the plan
 struct Plan {
     int total;      // N: tokens of the whole batch
-    int piece;      // C: tokens per piece
-    int n_active;   // pieces that hold at least one token
+    int n_pieces;   // pieces in use: min(launched pieces, N / minimum piece size), at least 1
 };
 
 __device__ __forceinline__ int clamp_len(int v) { return v > 0 ? v : 0; }
@@ -131,14 +130,28 @@ __device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ kv_lens, i
         total += wave_sum_i(i < batch ? clamp_len(kv_lens[i]) : 0);
     }
     total = __builtin_amdgcn_readfirstlane(total);
-    int c = (total + n_pieces - 1) / n_pieces;
-    if (c < min_piece) c = min_piece;
-    c = (c + kBlockKeys - 1) / kBlockKeys * kBlockKeys;
+    int n = total / min_piece;
+    n = n < 1 ? 1 : n;
     Plan pl;
     pl.total = total;
-    pl.piece = c;
-    pl.n_active = (total + c - 1) / c;
+    pl.n_pieces = n < n_pieces ? n : n_pieces;
     return pl;
+}
+
+// Piece p owns stream tokens [piece_bound(p), piece_bound(p + 1)): p * N / n_pieces rounded to a
+// multiple of the 16-key block, so every piece is within 16 tokens of N / n_pieces and all are used.
+__device__ __forceinline__ int piece_bound(const Plan& pl, int p) {
+    if (p >= pl.n_pieces) return pl.total;
+    const long x = (long)p * pl.total / pl.n_pieces;
+    const int r = (int)((x + kBlockKeys / 2) / kBlockKeys) * kBlockKeys;
+    return r < pl.total ? r : pl.total;
+}
+// The piece that owns stream token x (0 <= x < N).
+__device__ __forceinline__ int piece_of(const Plan& pl, int x) {
+    int p = (int)((long)x * pl.n_pieces / pl.total);
+    while (p + 1 < pl.n_pieces && piece_bound(pl, p + 1) <= x) ++p;
+    while (p > 0 && piece_bound(pl, p) > x) --p;
+    return p;
 }
 
 // One (piece, sequence) intersection as seen by one wave.
@@ -623,10 +636,11 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
 
     // Piece index: consecutive workgroups go to different XCDs, so give each XCD one contiguous
     // eighth of the token stream.
-    const int per_xcd = (pl.n_active + 7) >> 3;
+    const int per_xcd = (pl.n_pieces + 7) >> 3;
     const int bid = blockIdx.x;
     const int p = (bid & 7) * per_xcd + (bid >> 3);
-    const bool active = (bid >> 3) < per_xcd && p < pl.n_active;
+    const int s0 = piece_bound(pl, p), s1 = piece_bound(pl, p + 1);
+    const bool active = (bid >> 3) < per_xcd && p < pl.n_pieces && s0 < s1;
 
     if (bid == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64) {
         // For the merge kernel: first partial slot and number of segments of every sequence.
@@ -636,8 +650,8 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
             const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
             const int incl = wave_incl_scan_i(v, lane) + run;
             if (i < prm.batch) {
-                const int first = (incl - v) / pl.piece;
-                const int n_seg = v > 0 ? (incl - 1) / pl.piece - first + 1 : 0;
+                const int first = v > 0 ? piece_of(pl, incl - v) : 0;
+                const int n_seg = v > 0 ? piece_of(pl, incl - 1) - first + 1 : 0;
                 reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
             }
             run = __shfl(incl, 63, 64);
@@ -645,8 +659,6 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     }
     if (!active) return;
 
-    const int s0 = p * pl.piece;
-    const int s1 = (s0 + pl.piece < pl.total) ? s0 + pl.piece : pl.total;
 
     // Locate the sequence that holds stream token s0.
     int b = 0, j = 0;
