@@ -755,27 +755,31 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeParams prm) {
     }
     const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + (long)fs.x * stride_rows + th;
     const float2* po = reinterpret_cast<const float2*>(prm.part_o + ((long)fs.x * stride_rows + th) * kHeadDim) + lane;
-    float M = kNegInf;
-    for (int base = 0; base < n; base += 64) {
-        const int s = base + lane;
-        if (s < n) M = fmaxf(M, ml[s * stride_rows].x);
-    }
+    // Lane s holds (m_s, l_s) of slot s of the current group of 64 slots; the first 8 slots' partial
+    // rows are requested in the same breath, so a typical row (up to 8 segments) costs one round trip.
+    float2 mine = make_float2(kNegInf, 0.0f);
+    if (lane < n) mine = ml[lane * stride_rows];
+    float2 o[8];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, 64));
+    for (int u = 0; u < 8; ++u) o[u] = po[(u < n ? u : n - 1) * stride_rows * (kHeadDim / 2)];
+    float M = mine.x;
+    for (int base = 64; base < n; base += 64)
+        if (base + lane < n) M = fmaxf(M, ml[(base + lane) * stride_rows].x);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     const float m_use = (M == kNegInf) ? 0.0f : M;
     float l = 0.0f, o0 = 0.0f, o1 = 0.0f;
     for (int s0 = 0; s0 < n; s0 += 8) {
-        float2 a[8], o[8];
+        if (s0 > 0) {
+            if ((s0 & 63) == 0) mine = (s0 + lane < n) ? ml[(s0 + lane) * stride_rows] : make_float2(kNegInf, 0.0f);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int s = s0 + u < n ? s0 + u : n - 1;      // past the end: re-read the last slot, weight 0
-            a[u] = ml[s * stride_rows];
-            o[u] = po[s * stride_rows * (kHeadDim / 2)];
+            for (int u = 0; u < 8; ++u) o[u] = po[(s0 + u < n ? s0 + u : n - 1) * stride_rows * (kHeadDim / 2)];
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const float w = s0 + u < n ? fast_exp2(a[u].x - m_use) : 0.0f;
-            l = __builtin_fmaf(a[u].y, w, l);
+            const float m_s = __shfl(mine.x, (s0 + u) & 63, 64), l_s = __shfl(mine.y, (s0 + u) & 63, 64);
+            const float w = s0 + u < n ? fast_exp2(m_s - m_use) : 0.0f;      // past the end: weight 0
+            l = __builtin_fmaf(l_s, w, l);
             o0 = __builtin_fmaf(o[u].x, w, o0);
             o1 = __builtin_fmaf(o[u].y, w, o1);
         }
