@@ -161,6 +161,81 @@ int xtensor_chunk_order(void* handle, int32_t* order_out, int n);
  */
 int xtensor_physical_view(void* handle, void** view_out);
 
+/*
+ * xTensor page pool (section 4.3, "Physical Memory Page Management and Virtual Memory Tensor
+ * Management", "On-demand Memory Mapping", "Low Overhead Allocation").
+ *
+ * xtensor_pool_create  creates n_pages physical pages of XTENSOR_CHUNK_BYTES on `device` up front.
+ *                      Every page carries <PageID, Status, OwnerSession>; PageID is its index.
+ *                      Pages are handed out in a pseudo-random order drawn from `seed`.
+ * xtensor_pool_destroy unmaps Reusable sets and releases every page; fails with XATTN_EINVAL while
+ *                      a range is still open.
+ * xtensor_pool_counts  counts_out (HOST size_t[4]) receives the number of pages per status, indexed
+ *                      by XTENSOR_PAGE_*.
+ * xtensor_page_info    status and owner session of one page (outputs may be NULL).
+ *
+ * xtensor_open         a request's tensor: reserve `reserve_bytes` of virtual addresses (MaxSeqLen
+ *                      worth; nothing backed) and back the first `mapped_bytes`.  Page reuse: if a
+ *                      Reusable set of exactly ceil(mapped_bytes / page) pages sits in a range at
+ *                      least as large, that range is handed over as it is (no Map/Unmap call) and
+ *                      *reused_out = 1.  `session` is recorded as the pages' owner.
+ * xtensor_grow         on-demand mapping: make the first `mapped_bytes` of the range backed by
+ *                      mapping free pages at the next addresses; returns the number of pages newly
+ *                      mapped (>= 0).  When no page is free, the oldest Reusable set is unmapped
+ *                      first; with none left: XATTN_ENOMEM (the range keeps what it had).
+ * xtensor_premap_async the same request handed to the pool's background thread; returns at once.
+ *                      Meant to be called while the current decode step runs, for the pages the
+ *                      next tokens will need.  xtensor_premap_wait blocks until the range's requests
+ *                      are done and returns the last one's status.  xtensor_grow and xtensor_close
+ *                      wait for pending requests of their range first.
+ * xtensor_close        the request is finished.  keep_reusable != 0: the pages stay mapped and become
+ *                      Reusable (the handle stays known to the pool, not to the caller);
+ *                      keep_reusable == 0: unmap at once, pages become Free.
+ * xtensor_range_pages  page ids behind virtual pages 0, 1, ... of a range (HOST int64[n]); returns
+ *                      the count.  With the identity page = floor((va - base) / page_size) this is
+ *                      the whole address translation.
+ * Pool and ranges are thread-safe against each other; the caller makes sure no kernel uses a range
+ * that is being closed.  Errors as for xtensor_map.
+ */
+enum { XTENSOR_PAGE_FREE = 0, XTENSOR_PAGE_ALLOCATED = 1, XTENSOR_PAGE_MAPPED = 2, XTENSOR_PAGE_REUSABLE = 3 };
+int xtensor_pool_create(int device, size_t n_pages, uint64_t seed, void** pool_out);
+int xtensor_pool_destroy(void* pool);
+int xtensor_pool_counts(void* pool, size_t* counts_out);
+int xtensor_page_info(void* pool, size_t page_id, int* status_out, uint64_t* owner_out);
+int xtensor_open(void* pool, uint64_t session, size_t reserve_bytes, size_t mapped_bytes, void** base_out,
+                 void** range_out, int* reused_out);
+int xtensor_grow(void* range, size_t mapped_bytes);
+int xtensor_premap_async(void* range, size_t mapped_bytes);
+int xtensor_premap_wait(void* range);
+int xtensor_close(void* range, int keep_reusable);
+int xtensor_range_pages(void* range, int64_t* page_ids_out, int n);
+
+/*
+ * Testing hooks.  xtensor_test_fake_driver(1, fail_op, fail_after) replaces the HIP virtual-memory
+ * calls under the page pool by a host-only stand-in (addresses from a counter, no memory behind
+ * them), so that the pool's bookkeeping and its failure handling can be tested without a GPU;
+ * fail_op (-1 none, 1 reserve, 3 create, 5 map, 6 unmap) fails once after fail_after successful
+ * calls.  xtensor_test_fake_counts reports the stand-in's live reservations, pages and mappings.
+ * Never enable in a process that runs kernels on pool memory.
+ */
+int xtensor_test_fake_driver(int enable, int fail_op, int fail_after);
+int xtensor_test_fake_counts(size_t* reservations, size_t* handles, size_t* mappings);
+
+/*
+ * write_kvcache (section 4.3, "Operator Adaptation": the operator that appends new tokens' K and V
+ * takes the range's starting address and an offset, no block table).  Copies the q_len new rows of
+ * every sequence to rows [kv_lens[b] - q_len, kv_lens[b]) of its K and V ranges, i.e. kv_lens holds
+ * the lengths AFTER the append, the same array xattn_decode takes next.  Rows whose index would be
+ * negative are skipped.  The destination rows must be backed (xtensor_grow first).
+ * k_new, v_new  DEVICE bf16 [batch, q_len, n_kv_heads, head_dim], 16-byte aligned
+ * k_ptrs, v_ptrs DEVICE arrays[batch] of DEVICE pointers (as for xattn_decode, written here)
+ * kv_lens       DEVICE int32[batch].  Asynchronous on `stream`; head_dim * n_kv_heads * 2 must be a
+ * multiple of 16.
+ */
+int xattn_write_kvcache(const void* k_new, const void* v_new, void* const* k_ptrs, void* const* v_ptrs,
+                        const int32_t* kv_lens, int batch, int q_len, int n_kv_heads, int head_dim,
+                        void* stream);
+
 /* Synchronous copies between HOST memory and any DEVICE address (mapped ranges included). */
 int xtensor_upload(void* dst_device, const void* src_host, size_t bytes);
 int xtensor_download(void* dst_host, const void* src_device, size_t bytes);

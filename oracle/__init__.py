@@ -44,6 +44,8 @@ def _bind(path: str):
                                         i32, i32, i32, vp]
     lib.oracle_merge.restype = i32
     lib.oracle_merge.argtypes = [vp, vp, i32, ctypes.c_long, i32, vp, vp]
+    lib.oracle_write_kvcache.restype = i32
+    lib.oracle_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32]
     lib.oracle_page_of.restype = None
     lib.oracle_page_of.argtypes = [ctypes.c_uint64] * 3 + [vp, vp]
     return lib
@@ -153,3 +155,24 @@ def page_of(va: int, va_start: int, page_size: int) -> Tuple[int, int]:
     idx, off = ctypes.c_uint64(), ctypes.c_uint64()
     _load().oracle_page_of(va, va_start, page_size, ctypes.byref(idx), ctypes.byref(off))
     return int(idx.value), int(off.value)
+
+
+def write_kvcache(k_new: np.ndarray, v_new: np.ndarray, ks: Sequence[np.ndarray], vs: Sequence[np.ndarray],
+                  kv_lens: Sequence[int]) -> None:
+    """Append in place: k_new/v_new uint16 [B, T, Hkv, D] go to rows [kv_len - T, kv_len) of ks[b] / vs[b]."""
+    k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+    v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    B, T = k_new.shape[:2]
+    row = int(np.prod(k_new.shape[2:]))
+    for a in list(ks) + list(vs):
+        if a.dtype != np.uint16 or not a.flags["C_CONTIGUOUS"] or int(np.prod(a.shape[1:])) != row:
+            raise ValueError("K/V buffers must be contiguous uint16 [rows, Hkv, D]")
+    for b in range(B):
+        if ks[b].shape[0] < kv_lens[b] or vs[b].shape[0] < kv_lens[b]:
+            raise ValueError("buffer of sequence %d is shorter than kv_len" % b)
+    lens = np.ascontiguousarray(kv_lens, dtype=np.int32)
+    kp = (ctypes.c_void_p * max(B, 1))(*[k.ctypes.data for k in ks])
+    vp = (ctypes.c_void_p * max(B, 1))(*[v.ctypes.data for v in vs])
+    rc = _load().oracle_write_kvcache(k_new.ctypes.data, v_new.ctypes.data, kp, vp, lens.ctypes.data, B, T, row)
+    if rc != 0:
+        raise ValueError("oracle_write_kvcache rejected its arguments")

@@ -201,3 +201,25 @@ void oracle_page_of(uint64_t va, uint64_t va_start, uint64_t page_size, uint64_t
     *page_idx = (va - va_start) / page_size;
     *offset = (va - va_start) % page_size;
 }
+
+/*
+ * write_kvcache (section 4.3, "Operator Adaptation"): the q_len new K/V rows of sequence b go to rows
+ * [kv_lens[b] - q_len, kv_lens[b]) of its K and V ranges; kv_lens are the lengths after the append.
+ * k_new, v_new: bf16 [batch, q_len, row_elems]; k_ptrs[b], v_ptrs[b]: bf16 [>= kv_lens[b], row_elems].
+ */
+int oracle_write_kvcache(const uint16_t* k_new, const uint16_t* v_new, uint16_t* const* k_ptrs,
+                         uint16_t* const* v_ptrs, const int32_t* kv_lens, int batch, int q_len, int row_elems) {
+    if (!k_new || !v_new || !k_ptrs || !v_ptrs || !kv_lens || batch < 0 || q_len < 1 || row_elems < 1) return -1;
+    for (int b = 0; b < batch; ++b) {
+        if (kv_lens[b] < q_len) return -1;
+        for (int t = 0; t < q_len; ++t) {
+            const size_t dst = (size_t)(kv_lens[b] - q_len + t) * (size_t)row_elems;
+            const size_t src = ((size_t)b * q_len + t) * (size_t)row_elems;
+            for (int e = 0; e < row_elems; ++e) {
+                k_ptrs[b][dst + e] = k_new[src + e];
+                v_ptrs[b][dst + e] = v_new[src + e];
+            }
+        }
+    }
+    return 0;
+}

@@ -20,7 +20,11 @@ XTENSOR_CHUNK_BYTES = 2 << 20
 
 EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_set_workspace",
            "xattn_configure", "xattn_timing_read", "xtensor_map", "xtensor_unmap", "xtensor_chunk_order",
-           "xtensor_physical_view", "xtensor_upload", "xtensor_download"]
+           "xtensor_physical_view", "xtensor_upload", "xtensor_download",
+           "xtensor_pool_create", "xtensor_pool_destroy", "xtensor_pool_counts", "xtensor_page_info",
+           "xtensor_open", "xtensor_grow", "xtensor_premap_async", "xtensor_premap_wait", "xtensor_close",
+           "xtensor_range_pages", "xtensor_test_fake_driver", "xtensor_test_fake_counts", "xattn_write_kvcache"]
+XTENSOR_PAGE_FREE, XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_MAPPED, XTENSOR_PAGE_REUSABLE = 0, 1, 2, 3
 
 
 class XattnError(RuntimeError):
@@ -69,6 +73,32 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.xtensor_upload.argtypes = [vp, vp, sz]
     lib.xtensor_download.restype = i32
     lib.xtensor_download.argtypes = [vp, vp, sz]
+    lib.xtensor_pool_create.restype = i32
+    lib.xtensor_pool_create.argtypes = [i32, sz, u64, ctypes.POINTER(vp)]
+    lib.xtensor_pool_destroy.restype = i32
+    lib.xtensor_pool_destroy.argtypes = [vp]
+    lib.xtensor_pool_counts.restype = i32
+    lib.xtensor_pool_counts.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.xtensor_page_info.restype = i32
+    lib.xtensor_page_info.argtypes = [vp, sz, ctypes.POINTER(i32), ctypes.POINTER(u64)]
+    lib.xtensor_open.restype = i32
+    lib.xtensor_open.argtypes = [vp, u64, sz, sz, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i32)]
+    lib.xtensor_grow.restype = i32
+    lib.xtensor_grow.argtypes = [vp, sz]
+    lib.xtensor_premap_async.restype = i32
+    lib.xtensor_premap_async.argtypes = [vp, sz]
+    lib.xtensor_premap_wait.restype = i32
+    lib.xtensor_premap_wait.argtypes = [vp]
+    lib.xtensor_close.restype = i32
+    lib.xtensor_close.argtypes = [vp, i32]
+    lib.xtensor_range_pages.restype = i32
+    lib.xtensor_range_pages.argtypes = [vp, vp, i32]
+    lib.xtensor_test_fake_driver.restype = i32
+    lib.xtensor_test_fake_driver.argtypes = [i32, i32, i32]
+    lib.xtensor_test_fake_counts.restype = i32
+    lib.xtensor_test_fake_counts.argtypes = [ctypes.POINTER(sz)] * 3
+    lib.xattn_write_kvcache.restype = i32
+    lib.xattn_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     if path is None:
         _lib = lib
     return lib
@@ -160,3 +190,77 @@ def xtensor_upload(dst_device: int, src: np.ndarray) -> None:
 def xtensor_download(dst: np.ndarray, src_device: int) -> None:
     assert dst.flags["C_CONTIGUOUS"]
     _check(load_library().xtensor_download(dst.ctypes.data, src_device, dst.nbytes))
+
+
+def xtensor_pool_create(device: int, n_pages: int, seed: int) -> int:
+    pool = ctypes.c_void_p()
+    _check(load_library().xtensor_pool_create(device, n_pages, seed, ctypes.byref(pool)))
+    return int(pool.value)
+
+
+def xtensor_pool_destroy(pool: int) -> None:
+    _check(load_library().xtensor_pool_destroy(pool))
+
+
+def xtensor_pool_counts(pool: int) -> Tuple[int, int, int, int]:
+    """(free, allocated, mapped, reusable) pages."""
+    c = (ctypes.c_size_t * 4)()
+    _check(load_library().xtensor_pool_counts(pool, c))
+    return tuple(int(x) for x in c)
+
+
+def xtensor_page_info(pool: int, page_id: int) -> Tuple[int, int]:
+    """(status, owner session) of one page."""
+    st, owner = ctypes.c_int(), ctypes.c_uint64()
+    _check(load_library().xtensor_page_info(pool, page_id, ctypes.byref(st), ctypes.byref(owner)))
+    return int(st.value), int(owner.value)
+
+
+def xtensor_open(pool: int, session: int, reserve_bytes: int, mapped_bytes: int) -> Tuple[int, int, bool]:
+    """Returns (base device address, range handle, reused)."""
+    base, rng, reused = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_int()
+    _check(load_library().xtensor_open(pool, session, reserve_bytes, mapped_bytes, ctypes.byref(base),
+                                       ctypes.byref(rng), ctypes.byref(reused)))
+    return int(base.value), int(rng.value), bool(reused.value)
+
+
+def xtensor_grow(rng: int, mapped_bytes: int) -> int:
+    return _check(load_library().xtensor_grow(rng, mapped_bytes))
+
+
+def xtensor_premap_async(rng: int, mapped_bytes: int) -> None:
+    _check(load_library().xtensor_premap_async(rng, mapped_bytes))
+
+
+def xtensor_premap_wait(rng: int) -> None:
+    _check(load_library().xtensor_premap_wait(rng))
+
+
+def xtensor_close(rng: int, keep_reusable: bool) -> None:
+    _check(load_library().xtensor_close(rng, 1 if keep_reusable else 0))
+
+
+def xtensor_range_pages(rng: int) -> np.ndarray:
+    buf = np.empty(1 << 16, dtype=np.int64)
+    n = _check(load_library().xtensor_range_pages(rng, buf.ctypes.data, buf.size))
+    return buf[:n].copy()
+
+
+def xtensor_test_fake_driver(enable: bool, fail_op: int = -1, fail_after: int = 0) -> None:
+    _check(load_library().xtensor_test_fake_driver(1 if enable else 0, fail_op, fail_after))
+
+
+def xtensor_test_fake_counts() -> Tuple[int, int, int]:
+    """(live reservations, live pages, live mappings) of the host-only stand-in driver."""
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().xtensor_test_fake_counts(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
+    return int(a.value), int(b.value), int(c.value)
+
+
+def xattn_write_kvcache(k_new, v_new, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_kv_heads: int,
+                        head_dim: int, stream=None) -> None:
+    """Enqueue the append of q_len new K/V rows per sequence; see include/xattn.h."""
+    if stream is not None and not isinstance(stream, int):
+        stream = int(stream.cuda_stream)
+    _check(load_library().xattn_write_kvcache(_ptr(k_new), _ptr(v_new), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(kv_lens),
+                                              batch, q_len, n_kv_heads, head_dim, stream))

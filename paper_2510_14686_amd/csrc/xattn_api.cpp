@@ -259,6 +259,32 @@ int xattn_timing_read(int* n_calls, float* decode_kernel_ms, float* merge_kernel
     return XATTN_OK;
 }
 
+int xattn_write_kvcache(const void* k_new, const void* v_new, void* const* k_ptrs, void* const* v_ptrs,
+                        const int32_t* kv_lens, int batch, int q_len, int n_kv_heads, int head_dim, void* stream) {
+    if (!k_new || !v_new || !k_ptrs || !v_ptrs || !kv_lens)
+        return fail(XATTN_EINVAL, "xattn_write_kvcache: NULL argument");
+    if (batch < 1 || q_len < 1 || n_kv_heads < 1 || head_dim < 1)
+        return fail(XATTN_EINVAL, "xattn_write_kvcache: batch, q_len, n_kv_heads and head_dim must be positive");
+    const long row_bytes = (long)n_kv_heads * head_dim * 2;
+    if (row_bytes % 16 != 0 || row_bytes > (1 << 24))
+        return fail(XATTN_EUNSUPPORTED, "xattn_write_kvcache: a token row of %ld bytes is not a multiple of 16", row_bytes);
+    if (reinterpret_cast<uintptr_t>(k_new) % 16 != 0 || reinterpret_cast<uintptr_t>(v_new) % 16 != 0)
+        return fail(XATTN_EINVAL, "xattn_write_kvcache: k_new and v_new must be 16-byte aligned");
+    if ((long)batch * q_len > (1L << 30)) return fail(XATTN_EUNSUPPORTED, "xattn_write_kvcache: batch * q_len too large");
+    WriteParams prm;
+    prm.k_new = static_cast<const uint16_t*>(k_new);
+    prm.v_new = static_cast<const uint16_t*>(v_new);
+    prm.k_ptrs = k_ptrs;
+    prm.v_ptrs = v_ptrs;
+    prm.kv_lens = kv_lens;
+    prm.batch = batch;
+    prm.q_len = q_len;
+    prm.row_bytes = (int)row_bytes;
+    hipError_t e = launch_write_kvcache(prm, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return XATTN_OK;
+}
+
 int xtensor_upload(void* dst_device, const void* src_host, size_t bytes) {
     if (bytes == 0) return XATTN_OK;
     if (!dst_device || !src_host) return fail(XATTN_EINVAL, "xtensor_upload: NULL pointer");

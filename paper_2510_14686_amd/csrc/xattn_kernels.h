@@ -50,5 +50,17 @@ int rows_per_tile(int rows_total, int path);
 // holds three events, recorded before the decode kernel, between the kernels and after the merge.
 hipError_t launch_decode(const DecodeParams& prm, hipStream_t stream, hipEvent_t* events);
 
+// Appends q_len new K/V rows per sequence at rows [kv_lens[b] - q_len, kv_lens[b]).
+struct WriteParams {
+    const uint16_t* k_new;           // bf16 [batch, q_len, row_elems]
+    const uint16_t* v_new;
+    void* const* k_ptrs;
+    void* const* v_ptrs;
+    const int32_t* kv_lens;
+    int batch, q_len;
+    int row_bytes;                   // n_kv_heads * head_dim * 2
+};
+hipError_t launch_write_kvcache(const WriteParams& prm, hipStream_t stream);
+
 }  // namespace xattn
 #endif

@@ -789,6 +789,24 @@ __global__ __launch_bounds__(256) void merge_kernel(DecodeParams prm) {
     if (prm.lse && lane == 0) prm.lse[row] = l > 0.0f ? (M + __log2f(l)) * kLn2 : kNegInf;
 }
 
+// ---------------------------------------------------------------------------------- write_kvcache
+// One workgroup per (sequence, new token): copies the token's K row and V row (n_kv_heads * 256 bytes
+// each) to row kv_len - q_len + t of the sequence's ranges, 16 bytes per lane.
+__global__ __launch_bounds__(256) void write_kvcache_kernel(WriteParams prm) {
+    const int b = blockIdx.x / prm.q_len, t = blockIdx.x - b * prm.q_len;
+    const long pos = (long)prm.kv_lens[b] - prm.q_len + t;
+    if (pos < 0) return;
+    const long src = (long)blockIdx.x * prm.row_bytes;
+    char* kd = static_cast<char*>(prm.k_ptrs[b]) + pos * prm.row_bytes;
+    char* vd = static_cast<char*>(prm.v_ptrs[b]) + pos * prm.row_bytes;
+    const char* ks = reinterpret_cast<const char*>(prm.k_new) + src;
+    const char* vs = reinterpret_cast<const char*>(prm.v_new) + src;
+    for (int i = threadIdx.x * 16; i < prm.row_bytes; i += blockDim.x * 16) {
+        *reinterpret_cast<uint4*>(kd + i) = *reinterpret_cast<const uint4*>(ks + i);
+        *reinterpret_cast<uint4*>(vd + i) = *reinterpret_cast<const uint4*>(vs + i);
+    }
+}
+
 template <int R, bool kMatrix, int kPv = kPvBf16x2>
 hipError_t launch_decode_r(const DecodeParams& prm, dim3 grid, dim3 block, hipStream_t stream) {
     hipLaunchKernelGGL((split_decode_kernel<R, kMatrix, kPv>), grid, block, 0, stream, prm);
@@ -796,6 +814,11 @@ hipError_t launch_decode_r(const DecodeParams& prm, dim3 grid, dim3 block, hipSt
 }
 
 }  // namespace
+
+hipError_t launch_write_kvcache(const WriteParams& prm, hipStream_t stream) {
+    hipLaunchKernelGGL(write_kvcache_kernel, dim3((unsigned)(prm.batch * prm.q_len)), dim3(256), 0, stream, prm);
+    return hipGetLastError();
+}
 
 // Measured on MI355X: the matrix path is the faster one from 4 query rows per KV head upwards
 // (Qwen-style groups of 4, 5 and 8 at q_len 1, and every multi-token case); below that most of a

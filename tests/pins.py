@@ -308,7 +308,31 @@ def check_page_identity():
         assert oracle.page_of(start + off, start, page) == divmod(off, page)
 
 
+# 15 --------------------------------------------------------------------------------------
+def check_write_kvcache():
+    """Appending q_len new rows at rows [kv_len - q_len, kv_len): numpy slice assignment says the
+    same, rows outside the window and other sequences' buffers keep their bytes."""
+    B, T, Hkv = 3, 2, 2
+    lens = [5, 2, 9]
+    ks = [rnd(24, 1 + 2 * b, lens[b] + 3, Hkv, D) for b in range(B)]
+    vs = [rnd(24, 2 + 2 * b, lens[b] + 3, Hkv, D) for b in range(B)]
+    k_new, v_new = rnd(24, 50, B, T, Hkv, D), rnd(24, 51, B, T, Hkv, D)
+    want_k, want_v = [k.copy() for k in ks], [v.copy() for v in vs]
+    for b in range(B):
+        want_k[b][lens[b] - T:lens[b]] = k_new[b]
+        want_v[b][lens[b] - T:lens[b]] = v_new[b]
+    oracle.write_kvcache(k_new, v_new, ks, vs, lens)
+    for b in range(B):
+        np.testing.assert_array_equal(ks[b], want_k[b])
+        np.testing.assert_array_equal(vs[b], want_v[b])
+    try:
+        oracle.write_kvcache(k_new, v_new, ks, vs, [5, 1, 9])      # kv_len < q_len
+    except ValueError:
+        return
+    raise AssertionError("oracle accepted kv_len < q_len for write_kvcache")
+
+
 ALL_CHECKS = [check_single_key, check_identical_keys, check_weights_sum_to_one, check_zero_query,
               check_dominant_key, check_key_shift, check_causal_equals_sequential, check_merge_closed_forms,
               check_split_merge_identity, check_gqa_equals_mha_on_duplicated_heads, check_brute_force_tiny,
-              check_joint_permutation, check_against_scipy, check_rejects_bad_arguments, check_page_identity]
+              check_joint_permutation, check_against_scipy, check_rejects_bad_arguments, check_page_identity, check_write_kvcache]

@@ -33,6 +33,11 @@ MUTANTS = [
     ("merge_lse_without_max", "const double L = M + log(Z);", "const double L = log(Z);"),
     ("merge_counts_empty_parts", "if (l > -INFINITY) Z += exp(l - M);", "Z += 1.0;"),
     ("page_div_mod_swapped", "*page_idx = (va - va_start) / page_size;", "*page_idx = (va - va_start) % page_size;"),
+    ("write_kvcache_row_off_by_one", "const size_t dst = (size_t)(kv_lens[b] - q_len + t) * (size_t)row_elems;",
+     "const size_t dst = (size_t)(kv_lens[b] - q_len + t + 1) * (size_t)row_elems;"),
+    ("write_kvcache_v_gets_k", "v_ptrs[b][dst + e] = v_new[src + e];", "v_ptrs[b][dst + e] = k_new[src + e];"),
+    ("write_kvcache_source_ignores_token", "const size_t src = ((size_t)b * q_len + t) * (size_t)row_elems;",
+     "const size_t src = ((size_t)b * q_len) * (size_t)row_elems;"),
     ("token_order_in_q_index", "const int t = (int)((r / n_q_heads) % q_len);", "const int t = 0;"),
 ]
 
