@@ -148,6 +148,41 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline):
     return res
 
 
+def xtensor_page_ops(n_pages=256, reps=5):
+    """Host-side cost of the page operations of the xTensor pool, microseconds per 2 MiB page
+    (the paper's "Low Overhead Allocation": Map/Unmap are expensive, reuse and pre-mapping hide them)."""
+    import paper_2510_14686_amd as xa
+    page = xa.XTENSOR_CHUNK_BYTES
+    t = {"create_pool": [], "map_on_demand": [], "unmap": [], "reuse_open": [], "close_reusable": [],
+         "standalone_map": [], "standalone_unmap": []}
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        pool = xa.xtensor_pool_create(0, n_pages, 1)
+        t["create_pool"].append((time.perf_counter() - t0) / n_pages)
+        base, rng, _ = xa.xtensor_open(pool, 1, n_pages * page, 0)
+        t0 = time.perf_counter()
+        xa.xtensor_grow(rng, n_pages * page)
+        t["map_on_demand"].append((time.perf_counter() - t0) / n_pages)
+        t0 = time.perf_counter()
+        xa.xtensor_close(rng, True)
+        t["close_reusable"].append((time.perf_counter() - t0) / n_pages)
+        t0 = time.perf_counter()
+        base, rng, reused = xa.xtensor_open(pool, 2, n_pages * page, n_pages * page)
+        t["reuse_open"].append((time.perf_counter() - t0) / n_pages)
+        assert reused
+        t0 = time.perf_counter()
+        xa.xtensor_close(rng, False)
+        t["unmap"].append((time.perf_counter() - t0) / n_pages)
+        xa.xtensor_pool_destroy(pool)
+        t0 = time.perf_counter()
+        base, h = xa.xtensor_map(n_pages * page, n_pages * page, 7, 0)
+        t["standalone_map"].append((time.perf_counter() - t0) / n_pages)
+        t0 = time.perf_counter()
+        xa.xtensor_unmap(h)
+        t["standalone_unmap"].append((time.perf_counter() - t0) / n_pages)
+    return {k + "_us_per_page": round(1e6 * min(v), 3) for k, v in t.items()} | {"pages": n_pages, "page_bytes": page}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -162,6 +197,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
                          "the known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--xtensor", action="store_true",
+                    help="only time the xTensor page operations (map, unmap, reuse, pre-mapping) and print them")
     ap.add_argument("--check-sequences", type=int, default=None, help="sequences verified against the oracle (default all)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -193,6 +230,9 @@ def main():
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, args.min_piece_tokens)
     xa.xattn_configure(xa.XATTN_CFG_PATH, args.path)
     xa.xattn_configure(xa.XATTN_CFG_PV_MODE, args.pv_mode)
+    if args.xtensor:
+        print(json.dumps({"xtensor_page_ops": xtensor_page_ops()}), flush=True)
+        return
     head = workloads.CONFIGS[args.workload]
     main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True)
     others = {}

@@ -69,6 +69,12 @@ const char* xattn_last_error(void);
  * stream   hipStream_t (NULL = the default stream).  The call only enqueues work: it never
  *          synchronises and never reads device memory on the host.
  *
+ * Graph capture (section 4.2, "Integrating Custom Operators"): the call may be recorded into a HIP
+ * graph and replayed with other lengths, pointers and data in the same device buffers, since nothing
+ * on the host depends on their values.  The workspace must be large enough beforehand (one eager call
+ * of the shape, or xattn_set_workspace); a call that would have to grow it during capture returns
+ * XATTN_ENOMEM and records nothing.
+ *
  * Ownership: the caller owns every buffer and keeps it alive and unmodified until the enqueued work
  * has finished.  The library's workspace (see below) is shared by all calls on a device, so calls
  * on different streams of one device must not overlap in time.  On failure nothing is enqueued.

@@ -183,6 +183,14 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
         ws = static_cast<char*>(d->user_ws);
     } else {
         if (d->owned_bytes < w.total) {
+            // Growing allocates and synchronises, which a stream under graph capture forbids.
+            hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) == hipSuccess &&
+                capture != hipStreamCaptureStatusNone)
+                return fail(XATTN_ENOMEM,
+                            "xattn_decode: the workspace must grow to %zu bytes but the stream is being captured; "
+                            "run one call of this shape before the capture or hand over a workspace",
+                            w.total);
             // Work enqueued earlier may still use the old buffer: retire it before freeing.
             hipError_t e = hipDeviceSynchronize();
             if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");

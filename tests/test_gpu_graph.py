@@ -1,0 +1,119 @@
+"""xattn_decode and write_kvcache recorded into a HIP graph and replayed with other lengths and data
+(section 4.2: shapes reach custom operators as device-side arguments, so a recorded launch stays
+valid when they change).  Every replay is checked against the oracle and against an eager call, with
+eager work and synchronisations between the replays."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import normal_bf16
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+SCALE = float(np.float32(1.0 / math.sqrt(D)))
+
+
+def test_graph_replay_with_changing_lengths_and_data():
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    B, T, Hq, Hkv = 6, 2, 16, 4
+    cap = 6000
+    rounds = 5
+    ks = [normal_bf16(90, 1 + 2 * b, cap * Hkv * D).reshape(cap, Hkv, D) for b in range(B)]
+    vs = [normal_bf16(90, 2 + 2 * b, cap * Hkv * D).reshape(cap, Hkv, D) for b in range(B)]
+    with xa.KVStore(ks, vs, xtensor=True, seed=3) as store:
+        qd = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        kn = torch.zeros((B, T, Hkv, D), dtype=torch.int16, device="cuda")
+        vn = torch.zeros((B, T, Hkv, D), dtype=torch.int16, device="cuda")
+        lens_d = torch.full((B,), 100, dtype=torch.int32, device="cuda")
+        out = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((B, T, Hq), dtype=torch.float32, device="cuda")
+        out_e, lse_e = torch.zeros_like(out), torch.zeros_like(lse)
+        side = torch.cuda.Stream()
+        # one eager call of the shape sizes the library's workspace; a capture cannot grow it
+        with torch.cuda.stream(side):
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, lse, side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            xa.xattn_write_kvcache(kn, vn, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hkv, D, side)
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, lse, side)
+        rng = np.random.RandomState(5)
+        for r in range(rounds):
+            lens = rng.randint(T, cap - T, size=B)
+            lens[r % B] = [T, 17, cap - 1, 1024, 4097][r]           # edge lengths move around
+            q = normal_bf16(91, r, B * T * Hq * D).reshape(B, T, Hq, D)
+            k_new = normal_bf16(92, r, B * T * Hkv * D).reshape(B, T, Hkv, D)
+            v_new = normal_bf16(93, r, B * T * Hkv * D).reshape(B, T, Hkv, D)
+            qd.copy_(torch.from_numpy(q.view(np.int16)))
+            kn.copy_(torch.from_numpy(k_new.view(np.int16)))
+            vn.copy_(torch.from_numpy(v_new.view(np.int16)))
+            lens_d.copy_(torch.from_numpy(lens.astype(np.int32)))
+            out.fill_(0x7FC0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            oracle.write_kvcache(k_new, v_new, ks, vs, lens)       # the host copy follows the device's appends
+            ref_out, ref_lse = oracle.attn(q, ks, vs, lens, SCALE)
+            got, got_lse = out.cpu().numpy().view(np.uint16), lse.cpu().numpy()
+            assert_parity(got, got_lse, ref_out, ref_lse, "replay %d" % r)
+            # the same call issued eagerly gives the same bits
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out_e, lse_e,
+                            torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out_e.cpu().numpy().view(np.uint16), got)
+            np.testing.assert_array_equal(lse_e.cpu().numpy(), got_lse)
+            # the appended rows are in the device ranges
+            b = r % B
+            row = np.empty((T, Hkv, D), dtype=np.uint16)
+            xa.xtensor_download(row, store.k_addr[b] + (int(lens[b]) - T) * Hkv * D * 2)
+            np.testing.assert_array_equal(row, k_new[b])
+
+
+def test_capture_refuses_to_grow_the_workspace():
+    """A call that would have to enlarge the library's workspace while its stream is being captured
+    returns XATTN_ENOMEM and records nothing; the capture itself stays usable."""
+    import torch
+
+    import paper_2510_14686_amd as xa
+    B, T, Hq, Hkv = 2, 1, 8, 2
+    ks = [normal_bf16(94, 1 + 2 * b, 64 * Hkv * D).reshape(64, Hkv, D) for b in range(B)]
+    with xa.KVStore(ks, ks) as store:
+        qd = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        lens_d = torch.full((B,), 64, dtype=torch.int32, device="cuda")
+        out = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        marker = torch.zeros(8, device="cuda")
+        # a caller workspace that is too small stands for "the workspace would have to grow":
+        # the library may not replace it, captured or not
+        small = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+        xa.xattn_set_workspace(small, 4096)
+        try:
+            with pytest.raises(xa.XattnError) as e:
+                xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, None,
+                                torch.cuda.current_stream())
+            assert e.value.status == xa.binding.XATTN_ENOMEM
+        finally:
+            xa.xattn_set_workspace(None, 0)
+        # library-owned workspace, a shape larger than any call so far, under capture
+        xa.xattn_configure(xa.XATTN_CFG_PIECES, 4096)              # many pieces: a much larger workspace
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        status = None
+        try:
+            with torch.cuda.graph(graph, stream=side):
+                marker.add_(1.0)
+                try:
+                    xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, None, side)
+                except xa.XattnError as err:
+                    status = err.status
+        finally:
+            xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+        assert status == xa.binding.XATTN_ENOMEM
+        graph.replay()
+        torch.cuda.synchronize()
+        assert float(marker[0]) == 1.0                             # the capture recorded the rest and replays
