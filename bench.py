@@ -43,7 +43,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def run_workload(w, steps, warmup, check_rows, cpu_baseline):
+def run_workload(w, steps, warmup, check_rows, cpu_baseline, use_graph=False):
     import numpy as np
     import torch
 
@@ -78,6 +78,18 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline):
         for _ in range(warmup):
             step()
         torch.cuda.synchronize()
+        eager_step = step
+        if use_graph:
+            # one step recorded into a HIP graph; a timed step is one replay
+            side = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, w.scale, out, lse, side)
+            step = graph.replay
+            for _ in range(warmup):
+                step()
+            torch.cuda.synchronize()
+        res["launch"] = "hip graph replay" if use_graph else "eager"
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t_wall = time.perf_counter()
         e0.record(stream)
@@ -98,7 +110,7 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline):
         xa.xattn_timing_read()
         n_timed = min(steps, 2000)
         for _ in range(n_timed):
-            step()
+            eager_step()
         torch.cuda.synchronize()
         n, dec_ms, mrg_ms = xa.xattn_timing_read()
         xa.xattn_configure(xa.XATTN_CFG_TIMING, 0)
@@ -197,6 +209,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
                          "the known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
+    ap.add_argument("--graph", action="store_true", help="time replays of one HIP graph holding the call instead of eager calls")
     ap.add_argument("--xtensor", action="store_true",
                     help="only time the xTensor page operations (map, unmap, reuse, pre-mapping) and print them")
     ap.add_argument("--check-sequences", type=int, default=None, help="sequences verified against the oracle (default all)")
@@ -234,13 +247,13 @@ def main():
         print(json.dumps({"xtensor_page_ops": xtensor_page_ops()}), flush=True)
         return
     head = workloads.CONFIGS[args.workload]
-    main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True)
+    main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True, use_graph=args.graph)
     others = {}
     if not args.only:
         for name in workloads.CONFIG_ORDER:
             if name in ("tiny", args.workload):
                 continue
-            r = run_workload(workloads.CONFIGS[name], args.steps, args.warmup, 24, cpu_baseline=False)
+            r = run_workload(workloads.CONFIGS[name], args.steps, args.warmup, 24, cpu_baseline=False, use_graph=args.graph)
             others[name] = {k: r[k] for k in ("ms_per_step", "kv_read_GBps", "pct_of_hbm_peak", "token_steps_per_s",
                                               "kv_bytes", "kv_tokens", "batch", "q_len", "kv_placement", "parity")}
             others[name]["roofline"] = r["roofline"]
@@ -255,7 +268,8 @@ def main():
         "config": {"workload": main_res["workload"], "batch": main_res["batch"], "q_len": main_res["q_len"],
                    "n_q_heads": main_res["n_q_heads"], "n_kv_heads": main_res["n_kv_heads"],
                    "head_dim": main_res["head_dim"], "kv_tokens": main_res["kv_tokens"],
-                   "kv_bytes": main_res["kv_bytes"], "kv_placement": main_res["kv_placement"]},
+                   "kv_bytes": main_res["kv_bytes"], "kv_placement": main_res["kv_placement"],
+                   "launch": main_res["launch"]},
         "roofline": main_res["roofline"], "cpu_baseline": main_res.get("cpu_baseline"),
         "parity": main_res["parity"], "workloads": others,
     }
