@@ -32,10 +32,10 @@ HBM_PEAK_GBS = 8000.0
 # None until measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/split_decode_kernel__<workload>.txt: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 of the decode kernel
-    "qwen3_8b_decode": 646474913,
-    "long_context": 1628692004,
-    "spec_verify": 2460047248,
-    "skewed_xtensor": 2154813306,
+    "qwen3_8b_decode": 646598793,
+    "long_context": 1628775436,
+    "spec_verify": 2459933345,
+    "skewed_xtensor": 2154471091,
 }
 
 

@@ -100,7 +100,7 @@ def test_capture_refuses_to_grow_the_workspace():
         finally:
             xa.xattn_set_workspace(None, 0)
         # library-owned workspace, a shape larger than any call so far, under capture
-        xa.xattn_configure(xa.XATTN_CFG_PIECES, 4096)              # many pieces: a much larger workspace
+        xa.xattn_configure(xa.XATTN_CFG_PIECES, 65536)             # 64k pieces: a workspace larger than any earlier call left
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         status = None
