@@ -46,6 +46,8 @@ def _bind(path: str):
     lib.oracle_merge.argtypes = [vp, vp, i32, ctypes.c_long, i32, vp, vp]
     lib.oracle_write_kvcache.restype = i32
     lib.oracle_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32]
+    lib.oracle_mla.restype = i32
+    lib.oracle_mla.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp]
     lib.oracle_page_of.restype = None
     lib.oracle_page_of.argtypes = [ctypes.c_uint64] * 3 + [vp, vp]
     return lib
@@ -176,3 +178,24 @@ def write_kvcache(k_new: np.ndarray, v_new: np.ndarray, ks: Sequence[np.ndarray]
     rc = _load().oracle_write_kvcache(k_new.ctypes.data, v_new.ctypes.data, kp, vp, lens.ctypes.data, B, T, row)
     if rc != 0:
         raise ValueError("oracle_write_kvcache rejected its arguments")
+
+
+def mla(q: np.ndarray, cs: Sequence[np.ndarray], kv_lens: Sequence[int], d_v: int, scale: float
+        ) -> Tuple[np.ndarray, np.ndarray]:
+    """Latent-KV attention: q uint16 [B, T, H, d_qk]; cs[b] uint16 [>= kv_len, d_qk] is key and (its first
+    d_v columns) value of every head.  Returns (out float64 [B, T, H, d_v], lse float64 [B, T, H])."""
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    B, T, H, d_qk = q.shape
+    cs = [np.ascontiguousarray(c, dtype=np.uint16) for c in cs]
+    for b in range(B):
+        if cs[b].ndim != 2 or cs[b].shape[1] != d_qk or cs[b].shape[0] < kv_lens[b]:
+            raise ValueError("latent cache of sequence %d must be [>= kv_len, d_qk]" % b)
+    lens = np.ascontiguousarray(kv_lens, dtype=np.int32)
+    cp = (ctypes.c_void_p * max(B, 1))(*[c.ctypes.data for c in cs])
+    out = np.empty((B, T, H, d_v), dtype=np.float64)
+    lse = np.empty((B, T, H), dtype=np.float64)
+    rc = _load().oracle_mla(q.ctypes.data, cp, lens.ctypes.data, B, T, H, d_qk, d_v, ctypes.c_float(scale),
+                            out.ctypes.data, lse.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle_mla rejected its arguments")
+    return out, lse

@@ -223,3 +223,63 @@ int oracle_write_kvcache(const uint16_t* k_new, const uint16_t* v_new, uint16_t*
     }
     return 0;
 }
+
+/*
+ * Latent-KV (MLA-shaped) decode attention: the operator the paper itself adapts (section 4.3 "Operator
+ * Adaptation", section 4.4.1 "MLA Optimization").  Every head of a sequence reads the SAME cached row
+ * per token: the first d_v values of the row are the value vector, all d_qk values are the key
+ *     s_j = scale * sum_{d < d_qk} Q[b,t,h,d] * C_b[j,d]        j in [0, Lv),  Lv = kv_lens[b] - T + t + 1
+ *     out[b,t,h,:] = sum_j softmax(s)_j * C_b[j, 0:d_v]           lse = ln sum_j exp(s_j)
+ * q bf16 [batch, q_len, n_heads, d_qk]; c_ptrs[b] bf16 [>= kv_lens[b], d_qk]; out fp64 [batch, q_len,
+ * n_heads, d_v]; lse fp64 [batch, q_len, n_heads] (may be NULL).  Written out on its own (it does not
+ * call oracle_attn), two passes, fp64.
+ */
+int oracle_mla(const uint16_t* q, const uint16_t* const* c_ptrs, const int32_t* kv_lens, int batch, int q_len,
+               int n_heads, int d_qk, int d_v, float scale, double* out, double* lse) {
+    if (!q || !c_ptrs || !kv_lens || !out) return -1;
+    if (batch < 0 || q_len < 1 || n_heads < 1 || d_qk < 1 || d_v < 1 || d_v > d_qk) return -1;
+    int max_len = 0;
+    for (int b = 0; b < batch; ++b) {
+        if (kv_lens[b] < q_len) return -1;
+        if (kv_lens[b] > max_len) max_len = kv_lens[b];
+    }
+    const long rows = (long)batch * q_len * n_heads;
+    int failed = 0;
+#pragma omp parallel
+    {
+        double* p = (double*)malloc(sizeof(double) * (size_t)(max_len > 0 ? max_len : 1));
+        if (!p) {
+#pragma omp atomic write
+            failed = 1;
+        }
+#pragma omp for schedule(dynamic, 1)
+        for (long r = 0; r < rows; ++r) {
+            if (!p) continue;
+            const int t = (int)((r / n_heads) % q_len);
+            const int b = (int)(r / ((long)n_heads * q_len));
+            const int Lv = kv_lens[b] - q_len + t + 1;
+            const uint16_t* q_row = q + (size_t)r * d_qk;
+            const uint16_t* C = c_ptrs[b];
+            double m = -INFINITY;
+            for (int j = 0; j < Lv; ++j) {
+                double dot = 0.0;
+                for (int d = 0; d < d_qk; ++d) dot += bf16_to_f64(q_row[d]) * bf16_to_f64(C[(size_t)j * d_qk + d]);
+                p[j] = (double)scale * dot;
+                if (p[j] > m) m = p[j];
+            }
+            double Z = 0.0;
+            for (int j = 0; j < Lv; ++j) {
+                p[j] = exp(p[j] - m);
+                Z += p[j];
+            }
+            double* o = out + (size_t)r * d_v;
+            for (int d = 0; d < d_v; ++d) o[d] = 0.0;
+            for (int j = 0; j < Lv; ++j)
+                for (int d = 0; d < d_v; ++d) o[d] += p[j] * bf16_to_f64(C[(size_t)j * d_qk + d]);
+            for (int d = 0; d < d_v; ++d) o[d] /= Z;
+            if (lse) lse[r] = m + log(Z);
+        }
+        free(p);
+    }
+    return failed ? -1 : 0;
+}

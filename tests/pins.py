@@ -214,12 +214,12 @@ def check_gqa_equals_mha_on_duplicated_heads():
 # 10 --------------------------------------------------------------------------------------
 def brute_force_row(qrow, K, V, scale):
     """softmax(scale * K q) V for one row in pure Python, with exactly rounded sums."""
-    L, Dh = len(K), len(qrow)
+    L, Dh, Dv = len(K), len(qrow), len(V[0])
     s = [scale * math.fsum(qrow[d] * K[j][d] for d in range(Dh)) for j in range(L)]
     m = max(s)
     e = [math.exp(x - m) for x in s]
     Z = math.fsum(e)
-    out = [math.fsum(e[j] * V[j][d] for j in range(L)) / Z for d in range(Dh)]
+    out = [math.fsum(e[j] * V[j][d] for j in range(L)) / Z for d in range(Dv)]
     return out, m + math.log(Z)
 
 
@@ -332,7 +332,53 @@ def check_write_kvcache():
     raise AssertionError("oracle accepted kv_len < q_len for write_kvcache")
 
 
+# 16 --------------------------------------------------------------------------------------
+def check_mla_reduces_to_attention_with_one_shared_kv_head():
+    """Latent-KV attention is attention with one KV head whose K is the cached row and whose V is the
+    row's first d_v columns: the (separately written) oracle_mla must agree with the pinned
+    oracle_attn when d_v = d_qk, and its d_v < d_qk result must be the leading columns of that."""
+    B, T, H, Dq, Dv = 2, 2, 6, 128, 64
+    lens = [19, 40]
+    q = rnd(25, 0, B, T, H, Dq)
+    cs = [rnd(25, 1 + b, lens[b] + 2, Dq) for b in range(B)]
+    scale = 0.11
+    full_o, full_l = oracle.mla(q, cs, lens, Dq, scale)
+    ref_o, ref_l = oracle.attn(q, [c[:, None, :] for c in cs], [c[:, None, :] for c in cs], lens, scale)
+    np.testing.assert_allclose(full_o, ref_o, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(full_l, ref_l, rtol=0, atol=1e-13)
+    part_o, part_l = oracle.mla(q, cs, lens, Dv, scale)
+    np.testing.assert_array_equal(part_o, full_o[..., :Dv])
+    np.testing.assert_array_equal(part_l, full_l)
+    # heads differ, and the trailing key columns (the rope part) do matter
+    assert np.max(np.abs(full_l[..., 0] - full_l[..., 1])) > 1e-3
+    cs2 = [c.copy() for c in cs]
+    for c in cs2:
+        c[:, Dv:] = 0
+    assert np.max(np.abs(oracle.mla(q, cs2, lens, Dv, scale)[1] - part_l)) > 1e-3
+
+
+def check_mla_brute_force():
+    """oracle_mla against the pure-Python fsum evaluation and scipy, MLA-like odd sizes (d_qk = 72, d_v = 64)."""
+    B, T, H, Dq, Dv = 2, 3, 4, 72, 64
+    lens = [7, 4]
+    q = rnd(26, 0, B, T, H, Dq)
+    cs = [rnd(26, 1 + b, lens[b] + 1, Dq) for b in range(B)]
+    scale = float(np.float32(1.0 / math.sqrt(Dq)))
+    out, lse = oracle.mla(q, cs, lens, Dv, scale)
+    for b in range(B):
+        C = f64(cs[b])
+        for t in range(T):
+            Lv = lens[b] - T + t + 1
+            for h in range(H):
+                o, l = brute_force_row(list(f64(q[b, t, h])), C[:Lv].tolist(), C[:Lv, :Dv].tolist(), scale)
+                np.testing.assert_allclose(out[b, t, h], o, rtol=0, atol=1e-14)
+                assert abs(lse[b, t, h] - l) < 1e-14 * max(1.0, abs(l))
+                s_ = scale * (C[:Lv] @ f64(q[b, t, h]))
+                np.testing.assert_allclose(out[b, t, h], softmax(s_) @ C[:Lv, :Dv], rtol=0, atol=1e-13)
+
+
 ALL_CHECKS = [check_single_key, check_identical_keys, check_weights_sum_to_one, check_zero_query,
               check_dominant_key, check_key_shift, check_causal_equals_sequential, check_merge_closed_forms,
               check_split_merge_identity, check_gqa_equals_mha_on_duplicated_heads, check_brute_force_tiny,
-              check_joint_permutation, check_against_scipy, check_rejects_bad_arguments, check_page_identity, check_write_kvcache]
+              check_joint_permutation, check_against_scipy, check_rejects_bad_arguments, check_page_identity, check_write_kvcache,
+              check_mla_reduces_to_attention_with_one_shared_kv_head, check_mla_brute_force]

@@ -38,6 +38,14 @@ MUTANTS = [
     ("write_kvcache_v_gets_k", "v_ptrs[b][dst + e] = v_new[src + e];", "v_ptrs[b][dst + e] = k_new[src + e];"),
     ("write_kvcache_source_ignores_token", "const size_t src = ((size_t)b * q_len + t) * (size_t)row_elems;",
      "const size_t src = ((size_t)b * q_len) * (size_t)row_elems;"),
+    ("mla_value_uses_wrong_columns", "for (int d = 0; d < d_v; ++d) o[d] += p[j] * bf16_to_f64(C[(size_t)j * d_qk + d]);",
+     "for (int d = 0; d < d_v; ++d) o[d] += p[j] * bf16_to_f64(C[(size_t)j * d_qk + d + (d_qk - d_v)]);"),
+    ("mla_key_stops_at_value_width", "for (int d = 0; d < d_qk; ++d) dot += bf16_to_f64(q_row[d]) * bf16_to_f64(C[(size_t)j * d_qk + d]);",
+     "for (int d = 0; d < d_v; ++d) dot += bf16_to_f64(q_row[d]) * bf16_to_f64(C[(size_t)j * d_qk + d]);"),
+    ("mla_no_causal_mask", "const int Lv = kv_lens[b] - q_len + t + 1;\n            const uint16_t* q_row",
+     "const int Lv = kv_lens[b];\n            const uint16_t* q_row"),
+    ("mla_row_stride_is_value_width", "double dot = 0.0;\n                for (int d = 0; d < d_qk; ++d) dot += bf16_to_f64(q_row[d]) * bf16_to_f64(C[(size_t)j * d_qk + d]);",
+     "double dot = 0.0;\n                for (int d = 0; d < d_qk; ++d) dot += bf16_to_f64(q_row[d]) * bf16_to_f64(C[(size_t)j * d_v + d]);"),
     ("token_order_in_q_index", "const int t = (int)((r / n_q_heads) % q_len);", "const int t = 0;"),
 ]
 
