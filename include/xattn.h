@@ -84,6 +84,25 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
                  int head_dim, float scale, void* out, float* lse, void* stream);
 
 /*
+ * Latent-KV decode attention, the MLA-shaped operator the paper itself adapts (section 4.3
+ * "Operator Adaptation"; section 4.4.1 "MLA Optimization": with m speculated tokens, m+1 query
+ * tokens per sequence, all heads, are multiplied with the same cached rows).  Per token the cache
+ * holds ONE row of d_latent + d_rope bf16 shared by all heads: the whole row is every head's key, its
+ * first d_latent values are every head's value (K and V alias one buffer):
+ *     s_j = scale * <Q[b,t,h,:], C_b[j,:]>,  j < kv_lens[b] - q_len + t + 1
+ *     out[b,t,h,:] = sum_j softmax(s)_j * C_b[j, 0:d_latent]      lse[b,t,h] = ln sum_j exp(s_j)
+ * q       DEVICE bf16 [batch, q_len, n_heads, d_latent + d_rope]
+ * c_ptrs  DEVICE array[batch] of DEVICE pointers; c_ptrs[b] -> bf16 [>= kv_lens[b], d_latent + d_rope],
+ *         16-byte aligned; an xTensor range or any other device memory
+ * kv_lens DEVICE int32[batch], as for xattn_decode
+ * out     DEVICE bf16 [batch, q_len, n_heads, d_latent];  lse DEVICE fp32 [batch, q_len, n_heads] or NULL
+ * Supported: d_latent = 512, d_rope = 64, q_len * n_heads <= 4096, batch <= 4096; otherwise
+ * XATTN_EUNSUPPORTED.  Same partition, workspace, stream, capture and ownership rules as xattn_decode.
+ */
+int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv_lens, int batch, int q_len,
+                     int n_heads, int d_latent, int d_rope, float scale, void* out, float* lse, void* stream);
+
+/*
  * Workspace for the partial results of split sequences (section 4.4.3: the parts of a split
  * sequence are computed by different compute units and aggregated afterwards).
  * xattn_workspace_bytes: upper bound on the bytes one xattn_decode call of this shape uses.

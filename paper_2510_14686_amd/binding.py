@@ -23,7 +23,8 @@ EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_s
            "xtensor_physical_view", "xtensor_upload", "xtensor_download",
            "xtensor_pool_create", "xtensor_pool_destroy", "xtensor_pool_counts", "xtensor_page_info",
            "xtensor_open", "xtensor_grow", "xtensor_premap_async", "xtensor_premap_wait", "xtensor_close",
-           "xtensor_range_pages", "xtensor_test_fake_driver", "xtensor_test_fake_counts", "xattn_write_kvcache"]
+           "xtensor_range_pages", "xtensor_test_fake_driver", "xtensor_test_fake_counts", "xattn_write_kvcache",
+           "xattn_mla_decode"]
 XTENSOR_PAGE_FREE, XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_MAPPED, XTENSOR_PAGE_REUSABLE = 0, 1, 2, 3
 
 
@@ -97,6 +98,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.xtensor_test_fake_driver.argtypes = [i32, i32, i32]
     lib.xtensor_test_fake_counts.restype = i32
     lib.xtensor_test_fake_counts.argtypes = [ctypes.POINTER(sz)] * 3
+    lib.xattn_mla_decode.restype = i32
+    lib.xattn_mla_decode.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
     lib.xattn_write_kvcache.restype = i32
     lib.xattn_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     if path is None:
@@ -264,3 +267,12 @@ def xattn_write_kvcache(k_new, v_new, k_ptrs, v_ptrs, kv_lens, batch: int, q_len
         stream = int(stream.cuda_stream)
     _check(load_library().xattn_write_kvcache(_ptr(k_new), _ptr(v_new), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(kv_lens),
                                               batch, q_len, n_kv_heads, head_dim, stream))
+
+
+def xattn_mla_decode(q, c_ptrs, kv_lens, batch: int, q_len: int, n_heads: int, d_latent: int, d_rope: int,
+                     scale: float, out, lse=None, stream=None) -> None:
+    """Enqueue latent-KV (MLA-shaped) decode attention; see include/xattn.h."""
+    if stream is not None and not isinstance(stream, int):
+        stream = int(stream.cuda_stream)
+    _check(load_library().xattn_mla_decode(_ptr(q), _ptr(c_ptrs), _ptr(kv_lens), batch, q_len, n_heads, d_latent,
+                                           d_rope, ctypes.c_float(scale), _ptr(out), _ptr(lse), stream))

@@ -106,6 +106,55 @@ int device_state(DeviceState** out, int* dev_out) {
     return XATTN_OK;
 }
 
+// The device's workspace of at least `total` bytes: the caller's if one was handed over, else the
+// library's own, grown when needed (never while `stream` is being captured).
+int acquire_workspace(DeviceState* d, size_t total, hipStream_t stream, const char* who, char** ws_out) {
+    if (d->user_ws) {
+        if (d->user_bytes < total)
+            return fail(XATTN_ENOMEM, "%s: caller workspace has %zu bytes, this call needs %zu", who, d->user_bytes, total);
+        *ws_out = static_cast<char*>(d->user_ws);
+        return XATTN_OK;
+    }
+    if (d->owned_bytes < total) {
+        // Growing allocates and synchronises, which a stream under graph capture forbids.
+        hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(stream, &capture) == hipSuccess && capture != hipStreamCaptureStatusNone)
+            return fail(XATTN_ENOMEM,
+                        "%s: the workspace must grow to %zu bytes but the stream is being captured; "
+                        "run one call of this shape before the capture or hand over a workspace",
+                        who, total);
+        // Work enqueued earlier may still use the old buffer: retire it before freeing.
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
+        if (d->owned_ws) (void)hipFree(d->owned_ws);
+        d->owned_ws = nullptr;
+        d->owned_bytes = 0;
+        const size_t want = total + total / 4;
+        e = hipMalloc(&d->owned_ws, want);
+        if (e != hipSuccess) {
+            d->owned_ws = nullptr;
+            return fail_hip(e, "hipMalloc(workspace)");
+        }
+        d->owned_bytes = want;
+    }
+    *ws_out = static_cast<char*>(d->owned_ws);
+    return XATTN_OK;
+}
+
+// Events for the current call when timing is on (three per call), else null.
+int timing_events(hipEvent_t** events_out) {
+    *events_out = nullptr;
+    if (!g_cfg_timing || g_timed_calls >= kMaxTimedCalls) return XATTN_OK;
+    while ((int)g_events.size() < 3 * (g_timed_calls + 1)) {
+        hipEvent_t ev;
+        hipError_t ee = hipEventCreate(&ev);
+        if (ee != hipSuccess) return fail_hip(ee, "hipEventCreate");
+        g_events.push_back(ev);
+    }
+    *events_out = &g_events[3 * g_timed_calls];
+    return XATTN_OK;
+}
+
 }  // namespace
 }  // namespace xattn
 
@@ -176,37 +225,8 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
     const int n_pieces = pieces_for(d->n_cu);
     const WorkspaceLayout w = layout_for(batch, q_len, n_q_heads, n_pieces);
     char* ws = nullptr;
-    if (d->user_ws) {
-        if (d->user_bytes < w.total)
-            return fail(XATTN_ENOMEM, "xattn_decode: caller workspace has %zu bytes, this call needs %zu",
-                        d->user_bytes, w.total);
-        ws = static_cast<char*>(d->user_ws);
-    } else {
-        if (d->owned_bytes < w.total) {
-            // Growing allocates and synchronises, which a stream under graph capture forbids.
-            hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
-            if (hipStreamIsCapturing(static_cast<hipStream_t>(stream), &capture) == hipSuccess &&
-                capture != hipStreamCaptureStatusNone)
-                return fail(XATTN_ENOMEM,
-                            "xattn_decode: the workspace must grow to %zu bytes but the stream is being captured; "
-                            "run one call of this shape before the capture or hand over a workspace",
-                            w.total);
-            // Work enqueued earlier may still use the old buffer: retire it before freeing.
-            hipError_t e = hipDeviceSynchronize();
-            if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-            if (d->owned_ws) (void)hipFree(d->owned_ws);
-            d->owned_ws = nullptr;
-            d->owned_bytes = 0;
-            const size_t want = w.total + w.total / 4;
-            e = hipMalloc(&d->owned_ws, want);
-            if (e != hipSuccess) {
-                d->owned_ws = nullptr;
-                return fail_hip(e, "hipMalloc(workspace)");
-            }
-            d->owned_bytes = want;
-        }
-        ws = static_cast<char*>(d->owned_ws);
-    }
+    st = acquire_workspace(d, w.total, static_cast<hipStream_t>(stream), "xattn_decode", &ws);
+    if (st != XATTN_OK) return st;
 
     DecodeParams prm;
     prm.q = static_cast<const uint16_t*>(q);
@@ -231,15 +251,8 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
     prm.pv_mode = g_cfg_pv_mode;
 
     hipEvent_t* events = nullptr;
-    if (g_cfg_timing && g_timed_calls < kMaxTimedCalls) {
-        while ((int)g_events.size() < 3 * (g_timed_calls + 1)) {
-            hipEvent_t ev;
-            hipError_t ee = hipEventCreate(&ev);
-            if (ee != hipSuccess) return fail_hip(ee, "hipEventCreate");
-            g_events.push_back(ev);
-        }
-        events = &g_events[3 * g_timed_calls];
-    }
+    st = timing_events(&events);
+    if (st != XATTN_OK) return st;
     hipError_t e = launch_decode(prm, static_cast<hipStream_t>(stream), events);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     if (events) ++g_timed_calls;
@@ -264,6 +277,61 @@ int xattn_timing_read(int* n_calls, float* decode_kernel_ms, float* merge_kernel
     if (decode_kernel_ms) *decode_kernel_ms = decode_ms;
     if (merge_kernel_ms) *merge_kernel_ms = merge_ms;
     g_timed_calls = 0;
+    return XATTN_OK;
+}
+
+int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv_lens, int batch, int q_len,
+                     int n_heads, int d_latent, int d_rope, float scale, void* out, float* lse, void* stream) {
+    if (!q || !c_ptrs || !kv_lens || !out)
+        return fail(XATTN_EINVAL, "xattn_mla_decode: q, c_ptrs, kv_lens and out must not be NULL");
+    if (batch < 1 || q_len < 1 || n_heads < 1)
+        return fail(XATTN_EINVAL, "xattn_mla_decode: batch, q_len and n_heads must be positive");
+    if (d_latent != 512 || d_rope != 64)
+        return fail(XATTN_EUNSUPPORTED, "xattn_mla_decode: latent %d + rope %d: only 512 + 64 is supported", d_latent, d_rope);
+    if (batch > kMaxBatch) return fail(XATTN_EUNSUPPORTED, "batch %d exceeds %d", batch, kMaxBatch);
+    if (q_len > kMaxQLen) return fail(XATTN_EUNSUPPORTED, "q_len %d exceeds %d", q_len, kMaxQLen);
+    if ((long)q_len * n_heads > 4096) return fail(XATTN_EUNSUPPORTED, "q_len * n_heads = %ld exceeds 4096", (long)q_len * n_heads);
+    if (!std::isfinite(scale)) return fail(XATTN_EINVAL, "xattn_mla_decode: scale is not finite");
+    if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
+        return fail(XATTN_EINVAL, "xattn_mla_decode: q and out must be 16-byte aligned");
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* d = nullptr;
+    int st = device_state(&d, nullptr);
+    if (st != XATTN_OK) return st;
+    const int n_pieces = pieces_for(d->n_cu);
+    // same layout as the GQA path: per-sequence table, partial (m, l), partial rows of 512 fp32
+    const size_t slots = (size_t)n_pieces + (size_t)batch;
+    const size_t rows = (size_t)q_len * (size_t)n_heads;
+    const size_t ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
+    const size_t o_off = ml_off + align_up(slots * rows * 2 * sizeof(float), 256);
+    const size_t total = o_off + align_up(slots * rows * 512 * sizeof(float), 256);
+    char* ws = nullptr;
+    st = acquire_workspace(d, total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);
+    if (st != XATTN_OK) return st;
+
+    MlaParams prm;
+    prm.q = static_cast<const uint16_t*>(q);
+    prm.c_ptrs = c_ptrs;
+    prm.kv_lens = kv_lens;
+    prm.batch = batch;
+    prm.q_len = q_len;
+    prm.n_heads = n_heads;
+    prm.scale_log2 = (float)((double)scale * 1.4426950408889634074);
+    prm.out = static_cast<uint16_t*>(out);
+    prm.lse = lse;
+    prm.meta = reinterpret_cast<int32_t*>(ws);
+    prm.part_ml = reinterpret_cast<float*>(ws + ml_off);
+    prm.part_o = reinterpret_cast<float*>(ws + o_off);
+    prm.n_pieces = n_pieces;
+    prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
+    if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;
+    hipEvent_t* events = nullptr;
+    st = timing_events(&events);
+    if (st != XATTN_OK) return st;
+    hipError_t e = launch_mla_decode(prm, static_cast<hipStream_t>(stream), events);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (events) ++g_timed_calls;
     return XATTN_OK;
 }
 

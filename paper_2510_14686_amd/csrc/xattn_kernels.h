@@ -50,6 +50,24 @@ int rows_per_tile(int rows_total, int path);
 // holds three events, recorded before the decode kernel, between the kernels and after the merge.
 hipError_t launch_decode(const DecodeParams& prm, hipStream_t stream, hipEvent_t* events);
 
+// Latent-KV (MLA-shaped) decode: every head reads the same cached row of 576 bf16 per token.
+struct MlaParams {
+    const uint16_t* q;               // bf16 [batch, q_len, n_heads, 576]
+    const void* const* c_ptrs;       // device array[batch] of device pointers: bf16 [kv_len, 576]
+    const int32_t* kv_lens;
+    int batch, q_len, n_heads;
+    float scale_log2;
+    uint16_t* out;                   // bf16 [batch, q_len, n_heads, 512]
+    float* lse;                      // fp32 [batch, q_len, n_heads] or null
+    float* part_o;                   // fp32 [slots, q_len * n_heads, 512]
+    float* part_ml;                  // fp32 [slots, q_len * n_heads, 2]
+    int32_t* meta;                   // int32 [batch, 2]
+    int n_pieces, min_piece_tokens;
+};
+int mla_waves_per_block(int rows_total);
+// Enqueues the decode kernel and its merge kernel; events as for launch_decode.
+hipError_t launch_mla_decode(const MlaParams& prm, hipStream_t stream, hipEvent_t* events);
+
 // Appends q_len new K/V rows per sequence at rows [kv_lens[b] - q_len, kv_lens[b]).
 struct WriteParams {
     const uint16_t* k_new;           // bf16 [batch, q_len, row_elems]

@@ -32,7 +32,7 @@ class KVStore:
                 for which, (arr, addrs) in enumerate(((k, k_addr), (v, v_addr))):
                     arr = np.ascontiguousarray(arr, dtype=np.uint16)
                     if xtensor:
-                        row_bytes = arr.shape[1] * arr.shape[2] * 2
+                        row_bytes = int(np.prod(arr.shape[1:])) * 2
                         reserve = max(max_seq_len, arr.shape[0]) * row_bytes
                         base, handle = binding.xtensor_map(reserve, arr.nbytes, seed * 1000003 + 2 * b + which,
                                                            device)

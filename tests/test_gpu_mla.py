@@ -1,0 +1,108 @@
+"""Latent-KV (MLA-shaped) decode attention on the GPU against the fp64 oracle."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as wl
+from workloads import MLA_CONFIGS, bf16_to_f32, f32_to_bf16, normal_bf16
+
+pytestmark = pytest.mark.gpu
+
+DQK, DV = 576, 512
+SCALE = float(np.float32(1.0 / math.sqrt(192.0)))
+
+
+def gpu_mla(q, cs, lens, scale, xtensor=False, seed=0, want_lse=True):
+    import torch
+
+    import paper_2510_14686_amd as xa
+    B, T, H, _ = q.shape
+    with xa.KVStore(cs, cs, xtensor=xtensor, seed=seed) as store:
+        qd = torch.from_numpy(np.ascontiguousarray(q).view(np.int16)).cuda()
+        lens_d = torch.from_numpy(np.ascontiguousarray(lens, dtype=np.int32)).cuda()
+        out = torch.full((B, T, H, DV), 0x7FC0, dtype=torch.int16, device="cuda")
+        lse = torch.full((B, T, H), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+        xa.xattn_mla_decode(qd, store.k_ptrs, lens_d, B, T, H, 512, 64, scale, out, lse, torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        return out.cpu().numpy().view(np.uint16), (lse.cpu().numpy() if want_lse else None)
+
+
+def _case(seed, lens, T, H, extra=0):
+    B = len(lens)
+    q = f32_to_bf16(bf16_to_f32(normal_bf16(seed, 0, B * T * H * DQK)) * np.float32(math.sqrt(192.0 / DQK)))
+    q = q.reshape(B, T, H, DQK)
+    cs = [normal_bf16(seed, 1 + b, (L + extra) * DQK).reshape(L + extra, DQK) for b, L in enumerate(lens)]
+    return q, cs
+
+
+@pytest.fixture(autouse=True)
+def _default_partition():
+    import paper_2510_14686_amd as xa
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    yield
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+
+
+@pytest.mark.parametrize("T,H", [(1, 128), (2, 128), (1, 16), (1, 32), (3, 64), (1, 8), (2, 24), (1, 144)])
+def test_mla_shapes(T, H):
+    """Head counts from 8 to 144 (1 to 8 waves per workgroup, partial 16-row tiles, more than 128 rows:
+    two row groups) and 1 to 3 query tokens, ragged lengths around the 16-key block."""
+    from gpu_util import assert_parity
+    lens = [T, T + 1, 15 + T, 16 + T, 17 + T, 64, 65, 200, 333, 1500]
+    q, cs = _case(200 + T, lens, T, H)
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla T=%d H=%d" % (T, H))
+
+
+@pytest.mark.parametrize("pieces,min_piece", [(8, 16), (256, 16), (1024, 16), (1, 0), (37, 48)])
+def test_mla_result_does_not_depend_on_the_partition(pieces, min_piece):
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    lens = [700, 33, 2, 2049, 16, 512, 90]
+    q, cs = _case(210, lens, 2, 32)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE)
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, pieces)
+    xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, min_piece)
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla pieces=%d" % pieces)
+
+
+def test_mla_xtensor_equals_plain_and_rows_past_kv_len_are_not_read():
+    from gpu_util import assert_parity
+    lens = [3000, 1025, 40, 1821]          # 1152 B per token: about 1820 tokens per 2 MiB chunk
+    q, cs = _case(211, lens, 1, 64, extra=30)
+    for b, L in enumerate(lens):
+        cs[b][L:] = 0x7FC0                  # NaN past the end
+    a_out, a_lse = gpu_mla(q, cs, lens, SCALE, xtensor=False)
+    b_out, b_lse = gpu_mla(q, cs, lens, SCALE, xtensor=True, seed=4)
+    np.testing.assert_array_equal(a_out, b_out)
+    np.testing.assert_array_equal(a_lse, b_lse)
+    ref_out, ref_lse = oracle.mla(q, [c[:L] for c, L in zip(cs, lens)], lens, DV, SCALE)
+    assert_parity(a_out, a_lse, ref_out, ref_lse, "mla padded")
+
+
+def test_mla_argument_checks():
+    import paper_2510_14686_amd as xa
+    for args in ((1, 1, 16, 512, 32), (1, 1, 16, 256, 64), (1, 17, 16, 512, 64), (1, 16, 512, 512, 64)):
+        with pytest.raises(xa.XattnError) as e:
+            xa.xattn_mla_decode(16, 16, 16, *args, 0.1, 16)
+        assert e.value.status == xa.binding.XATTN_EUNSUPPORTED
+    with pytest.raises(xa.XattnError) as e:
+        xa.xattn_mla_decode(0, 16, 16, 1, 1, 16, 512, 64, 0.1, 16)
+    assert e.value.status == xa.binding.XATTN_EINVAL
+
+
+@pytest.mark.parametrize("name", ["mla_decode", "mla_verify"])
+def test_mla_scaled_down_workloads(name):
+    from gpu_util import assert_parity
+    w = MLA_CONFIGS[name].scaled(name + "_small", 6, 8)
+    lens = w.kv_lens()
+    q, cs = w.make_q(), w.make_cache(lens)
+    out_bits, lse = gpu_mla(q, cs, lens, w.scale, xtensor=True, seed=w.seed)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, w.d_latent, w.scale)
+    assert_parity(out_bits, lse, ref_out, ref_lse, w.name)

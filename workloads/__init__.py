@@ -175,6 +175,70 @@ class Workload:
         return replace(self, name=name, batch=batch, len_args=args)
 
 
+@dataclass(frozen=True)
+class MlaWorkload:
+    """Latent-KV (MLA-shaped) decode: one cached row of d_latent + d_rope values per token, shared by all heads."""
+    name: str
+    batch: int
+    q_len: int
+    n_heads: int
+    seed: int
+    len_args: Tuple            # uniform (lo, hi) cached-prefix length
+    d_latent: int = 512
+    d_rope: int = 64
+    xtensor: bool = True
+    note: str = ""
+
+    @property
+    def d_qk(self) -> int:
+        return self.d_latent + self.d_rope
+
+    @property
+    def scale(self) -> float:
+        """1/sqrt(128 + 64): the softmax scale of a model whose un-absorbed head has 128 + 64 dimensions."""
+        return float(np.float32(1.0 / math.sqrt(192.0)))
+
+    def kv_lens(self) -> np.ndarray:
+        lo, hi = self.len_args
+        u = uniform_u64(self.seed, _LEN_STREAM, self.batch)
+        lens = lo + (u % np.uint64(hi - lo + 1)).astype(np.int64)
+        return (lens + (self.q_len if self.q_len > 1 else 0)).astype(np.int32)
+
+    def kv_bytes(self, lens=None) -> int:
+        lens = self.kv_lens() if lens is None else lens
+        return int(np.sum(np.asarray(lens, dtype=np.int64))) * self.d_qk * 2
+
+    def flops(self, lens=None) -> int:
+        """2 * (d_qk + d_latent) per key, row and head (the causal trim of the last q_len - 1 keys ignored)."""
+        lens = self.kv_lens() if lens is None else lens
+        return int(np.sum(np.asarray(lens, dtype=np.int64))) * self.q_len * self.n_heads * 2 * (self.d_qk + self.d_latent)
+
+    def make_q(self) -> np.ndarray:
+        """Queries scaled so that scores have unit variance, as trained attention has: N(0,1) / sqrt(d_qk / 192)."""
+        n = self.batch * self.q_len * self.n_heads * self.d_qk
+        z = bf16_to_f32(normal_bf16(self.seed, 0, n)) * np.float32(math.sqrt(192.0 / self.d_qk))
+        return f32_to_bf16(z).reshape(self.batch, self.q_len, self.n_heads, self.d_qk)
+
+    def make_c(self, b: int, length: int) -> np.ndarray:
+        return normal_bf16(self.seed, 1 + b, length * self.d_qk).reshape(length, self.d_qk)
+
+    def make_cache(self, lens=None):
+        lens = self.kv_lens() if lens is None else lens
+        return [self.make_c(b, int(L)) for b, L in enumerate(lens)]
+
+    def scaled(self, name: str, batch: int, len_div: int, n_heads: Optional[int] = None) -> "MlaWorkload":
+        lo, hi = self.len_args
+        return replace(self, name=name, batch=batch, len_args=(max(1, lo // len_div), max(2, hi // len_div)),
+                       n_heads=self.n_heads if n_heads is None else n_heads)
+
+
+MLA_CONFIGS = {
+    "mla_decode": MlaWorkload("mla_decode", 64, 1, 128, seed=5, len_args=(1024, 8192),
+                              note="DeepSeek-style latent KV, 128 heads under DP attention, plain decode"),
+    "mla_verify": MlaWorkload("mla_verify", 64, 2, 128, seed=6, len_args=(1024, 8192),
+                              note="one speculated token (MTP): 2 query tokens per sequence"),
+}
+
 CONFIGS = {
     "tiny": Workload("tiny", 4, 1, 8, 2, 128, seed=0, len_kind="fixed", len_args=(17, 64, 100, 256),
                      note="parity / latency only"),
