@@ -160,6 +160,85 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline, use_graph=False):
     return res
 
 
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def run_mla_workload(w, steps, warmup, check_rows):
+    """Latent-KV (MLA-shaped) decode: same protocol as run_workload; the roofline is the bf16 matrix peak."""
+    import numpy as np
+    import torch
+
+    import oracle
+    import paper_2510_14686_amd as xa
+    from gpu_util import errors
+    t0 = time.time()
+    lens = w.kv_lens()
+    q = w.make_q()
+    cs = w.make_cache(lens)
+    kv_bytes, flops = w.kv_bytes(lens), w.flops(lens)
+    log("[%s] generated %.2f GB of latent cache for %d sequences in %.1f s" % (w.name, kv_bytes / 1e9, w.batch, time.time() - t0))
+    B, T, H = w.batch, w.q_len, w.n_heads
+    res = {"workload": w.name, "batch": B, "q_len": T, "n_heads": H, "d_latent": w.d_latent, "d_rope": w.d_rope,
+           "kv_tokens": int(lens.sum()), "kv_bytes": kv_bytes, "flops": flops}
+    store = xa.KVStore(cs, cs, device=0, xtensor=w.xtensor, seed=w.seed)
+    try:
+        qd = torch.from_numpy(np.ascontiguousarray(q).view(np.int16)).cuda()
+        lens_d = torch.from_numpy(lens).cuda()
+        out = torch.zeros((B, T, H, w.d_latent), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((B, T, H), dtype=torch.float32, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def step():
+            xa.xattn_mla_decode(qd, store.k_ptrs, lens_d, B, T, H, w.d_latent, w.d_rope, w.scale, out, lse, stream)
+
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 0)
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            step()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms_step = e0.elapsed_time(e1) / steps
+        res["ms_per_step"] = ms_step
+        res["kv_read_GBps"] = kv_bytes / (ms_step * 1e-3) / 1e9
+        res["pct_of_hbm_peak"] = 100.0 * res["kv_read_GBps"] / HBM_PEAK_GBS
+        res["tflops"] = flops / (ms_step * 1e-3) / 1e12
+        res["token_steps_per_s"] = B * T / (ms_step * 1e-3)
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 1)
+        xa.xattn_timing_read()
+        for _ in range(min(steps, 1000)):
+            step()
+        torch.cuda.synchronize()
+        n, dec_ms, mrg_ms = xa.xattn_timing_read()
+        xa.xattn_configure(xa.XATTN_CFG_TIMING, 0)
+        dec_ms_avg, mrg_ms_avg = dec_ms / max(n, 1), mrg_ms / max(n, 1)
+        achieved = flops / (dec_ms_avg * 1e-3) / 1e12
+        res["roofline"] = {"kernel": "mla_decode_kernel", "bound": "mfma", "achieved": achieved,
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get(w.name), "algorithmic_flops_per_launch": flops,
+                           "algorithmic_bytes_per_launch": kv_bytes, "kernel_ms": dec_ms_avg,
+                           "merge_kernel_ms": mrg_ms_avg, "timed_launches": n,
+                           "hbm_GBps_of_kernel": kv_bytes / (dec_ms_avg * 1e-3) / 1e9}
+        out_h = out.cpu().numpy().view(np.uint16)
+        lse_h = lse.cpu().numpy()
+        sel = list(range(B)) if check_rows is None or check_rows >= B else \
+            sorted(set(np.linspace(0, B - 1, check_rows).astype(int).tolist() + [int(np.argmax(lens)), int(np.argmin(lens))]))
+        ref_out, ref_lse = oracle.mla(q[sel], [cs[b] for b in sel], lens[sel], w.d_latent, w.scale)
+        max_abs, rel_rows, rel_all, lse_err = errors(out_h[sel], lse_h[sel], ref_out, ref_lse)
+        res["parity"] = {"sequences_checked": len(sel), "max_abs": max_abs, "max_row_rel_l2": rel_rows,
+                         "rel_l2": rel_all, "lse_max_abs": lse_err,
+                         "pass": bool(max_abs <= 1e-2 and rel_rows <= 5e-3 and lse_err <= 1e-3)}
+        log("[%s] %.1f us/step  %.0f GB/s (%.1f%% of HBM peak)  %.0f TFLOP/s  kernel %.1f us -> %.0f TFLOP/s (%.1f%% of bf16 MFMA peak)  merge %.1f us  parity %s"
+            % (w.name, ms_step * 1e3, res["kv_read_GBps"], res["pct_of_hbm_peak"], res["tflops"], dec_ms_avg * 1e3,
+               achieved, 100 * achieved / MFMA_BF16_PEAK_TFLOPS, mrg_ms_avg * 1e3, res["parity"]))
+    finally:
+        store.close()
+    return res
+
+
 def xtensor_page_ops(n_pages=256, reps=5):
     """Host-side cost of the page operations of the xTensor pool, microseconds per 2 MiB page
     (the paper's "Low Overhead Allocation": Map/Unmap are expensive, reuse and pre-mapping hide them)."""
@@ -205,6 +284,7 @@ def main():
     ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
     ap.add_argument("--min-piece-tokens", type=int, default=0, help="override the minimum piece size (0 = default)")
     ap.add_argument("--path", type=int, default=0, help="inner loop: 0 automatic, 1 vector, 2 matrix cores")
+    ap.add_argument("--mla-layout", type=int, default=0, help="latent-KV kernel: 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave")
     ap.add_argument("--pv-mode", type=int, default=0, help="matrix path p.V product: 0 default (bf16 MFMA, hi+lo parts), 1 fp32 MFMA, 2 single bf16 MFMA")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
@@ -243,8 +323,20 @@ def main():
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, args.min_piece_tokens)
     xa.xattn_configure(xa.XATTN_CFG_PATH, args.path)
     xa.xattn_configure(xa.XATTN_CFG_PV_MODE, args.pv_mode)
+    xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, args.mla_layout)
     if args.xtensor:
         print(json.dumps({"xtensor_page_ops": xtensor_page_ops()}), flush=True)
+        return
+    if args.workload in workloads.MLA_CONFIGS:
+        r = run_mla_workload(workloads.MLA_CONFIGS[args.workload], args.steps, args.warmup, args.check_sequences or 8)
+        print(json.dumps({"metric": "latent-KV decode attention: TFLOP/s (bf16 MFMA) + KV-read GB/s, 1 MI355X",
+                          "value": r["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                          "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                          "dtype": "bf16 in/out, fp32 accumulate", "data": "synthetic (seeded N(0,1) bf16, seeded lengths)",
+                          "config": {k: r[k] for k in ("workload", "batch", "q_len", "n_heads", "d_latent", "d_rope",
+                                                       "kv_tokens", "kv_bytes", "flops")},
+                          "kv_read_GBps": r["kv_read_GBps"], "token_steps_per_s": r["token_steps_per_s"],
+                          "roofline": r["roofline"], "parity": r["parity"]}), flush=True)
         return
     head = workloads.CONFIGS[args.workload]
     main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True, use_graph=args.graph)

@@ -130,10 +130,13 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *                               MFMA on hi + lo bf16 parts of the weights (16 significant bits);
  *                               1 = fp32 MFMA (weights exact, slower); 2 = one bf16 MFMA (weights
  *                               rounded to bf16)
+ *                               (xattn_mla_decode: 0 and 1 = hi + lo parts, 2 = one bf16 MFMA)
+ *   XATTN_CFG_MLA_LAYOUT        xattn_mla_decode workgroup shape: 0 = automatic, 1 = one 16-row tile per
+ *                               wave (up to 8 waves), 2 = two tiles per wave (4 waves, from 128 rows)
  * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
  */
 enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3,
-       XATTN_CFG_PV_MODE = 4 };
+       XATTN_CFG_PV_MODE = 4, XATTN_CFG_MLA_LAYOUT = 5 };
 int xattn_configure(int key, int value);
 
 /*

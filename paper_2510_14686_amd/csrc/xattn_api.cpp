@@ -51,6 +51,7 @@ int g_cfg_min_piece = 0;
 int g_cfg_timing = 0;
 int g_cfg_path = 0;
 int g_cfg_pv_mode = 0;
+int g_cfg_mla_layout = 0;
 
 constexpr int kMaxTimedCalls = 4096;
 std::vector<hipEvent_t> g_events;     // three per timed call, created on demand, reused across series
@@ -174,6 +175,10 @@ int xattn_configure(int key, int value) {
         case XATTN_CFG_PATH:
             if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: path %d is not 0, 1 or 2", value);
             g_cfg_path = value;
+            return XATTN_OK;
+        case XATTN_CFG_MLA_LAYOUT:
+            if (value > 3) return fail(XATTN_EINVAL, "xattn_configure: MLA layout %d is not 0..3", value);
+            g_cfg_mla_layout = value;
             return XATTN_OK;
         case XATTN_CFG_PV_MODE:
             if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: pv mode %d is not 0, 1 or 2", value);
@@ -326,6 +331,8 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;
+    prm.layout = g_cfg_mla_layout;
+    prm.hi_lo = g_cfg_pv_mode == 2 ? 0 : 1;       // XATTN_CFG_PV_MODE 2 rounds the weights to one bf16
     hipEvent_t* events = nullptr;
     st = timing_events(&events);
     if (st != XATTN_OK) return st;

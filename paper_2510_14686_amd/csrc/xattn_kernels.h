@@ -63,8 +63,10 @@ struct MlaParams {
     float* part_ml;                  // fp32 [slots, q_len * n_heads, 2]
     int32_t* meta;                   // int32 [batch, 2]
     int n_pieces, min_piece_tokens;
+    int layout;                      // 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave
+    int hi_lo;                       // softmax weights into the value product as hi + lo bf16 parts
 };
-int mla_waves_per_block(int rows_total);
+void mla_block_shape(int rows_total, int layout, int* waves, int* tiles_per_wave);
 // Enqueues the decode kernel and its merge kernel; events as for launch_decode.
 hipError_t launch_mla_decode(const MlaParams& prm, hipStream_t stream, hipEvent_t* events);
 
