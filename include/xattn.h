@@ -131,8 +131,9 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *                               1 = fp32 MFMA (weights exact, slower); 2 = one bf16 MFMA (weights
  *                               rounded to bf16)
  *                               (xattn_mla_decode: 0 and 1 = hi + lo parts, 2 = one bf16 MFMA)
- *   XATTN_CFG_MLA_LAYOUT        xattn_mla_decode workgroup shape: 0 = automatic, 1 = one 16-row tile per
- *                               wave (up to 8 waves), 2 = two tiles per wave (4 waves, from 128 rows)
+ *   XATTN_CFG_MLA_LAYOUT        xattn_mla_decode workgroup shape for more than 64 query rows per sequence:
+ *                               0 = automatic (8 waves of one 16-row tile), 1 = 4 waves of one tile,
+ *                               2 = 4 waves of two tiles; for experiments, results do not depend on it
  * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
  */
 enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3,

@@ -177,7 +177,7 @@ int xattn_configure(int key, int value) {
             g_cfg_path = value;
             return XATTN_OK;
         case XATTN_CFG_MLA_LAYOUT:
-            if (value > 3) return fail(XATTN_EINVAL, "xattn_configure: MLA layout %d is not 0..3", value);
+            if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: MLA layout %d is not 0, 1 or 2", value);
             g_cfg_mla_layout = value;
             return XATTN_OK;
         case XATTN_CFG_PV_MODE:

@@ -8,19 +8,26 @@
 // cached byte: the path is bound by the matrix cores and by the LDS that feeds them, not by HBM.
 //
 // Partition: the same token-stream pieces as the GQA kernel (section 4.4.3, "Layer 3").  A workgroup
-// owns one piece and up to 128 query rows (row = token * n_heads + head): wave w owns rows 16w..16w+15,
-// keeps their Q (72 VGPRs) and their output accumulators (16 x 512 fp32 = 128 VGPRs) in registers for
-// the whole piece, and all waves share each 16-key block of the cache through LDS:
-//   * the block (16 x 1152 bytes, contiguous in memory) goes from HBM straight into LDS (buffer loads
+// owns one piece and up to 128 query rows (row = token * n_heads + head).  It has at most four waves,
+// one per SIMD, so that a wave may use the whole 512-entry register file: a wave owns one or two
+// tiles of 16 rows and keeps their Q (72 registers per tile) and their output accumulators (16 x 512
+// fp32 = 128 registers per tile) resident for the whole piece.  All waves share each 32-key block of
+// the cache through LDS:
+//   * the block (32 x 1152 bytes, contiguous in memory) goes from HBM straight into LDS (buffer loads
 //     with the LDS destination, 1 KiB per wave instruction, no staging registers), once per
 //     workgroup, two LDS buffers, one barrier per block, the next block in flight during the
-//     arithmetic; 16-byte chunks are XOR-swizzled by row (through the global address each lane
-//     fetches, since the LDS side of such a load is fixed to lane order) against bank conflicts;
-//   * S^T = C Q^T: 18 bf16 MFMA 16x16x32 on two accumulators, the A operand read from LDS;
-//   * softmax on the accumulator layout, as in the GQA matrix path;
-//   * O^T += C[:, 0:512]^T P^T: per 128-column group a lane reads the same 8 columns of its four keys
-//     (4 x 128 bits) and builds the A operands of 8 column tiles with byte permutes; P goes in as
-//     hi + lo bf16 parts (bf16 MFMA 16x16x16).
+//     arithmetic.  Rows sit 1184 bytes apart in LDS (two 16-byte pad chunks; the pad is made through
+//     the global address each lane fetches, since the LDS side of such a load is fixed to lane order):
+//     measured, a pitch of 2 * odd chunks modulo 16 serves both read patterns below without bank
+//     conflicts, an odd pitch (1168) halves the rate of both;
+//   * S^T = C Q^T: per 16-key tile 18 bf16 MFMA 16x16x32, the A operand (keys) read from LDS and used
+//     for both row tiles of the wave;
+//   * softmax on the accumulator layout: lane (kb, n) holds, of row n, the keys 4 kb + i of both key
+//     tiles, which is exactly the B operand (8 keys per lane) of the next product, so the weights
+//     never leave the lane; row maxima cross the four lane groups with lane-swap instructions;
+//   * O^T += C[:, 0:512]^T P^T: bf16 MFMA 16x16x32 over the 32 keys, the A operand (16 value columns x
+//     8 keys per lane) fetched with LDS transposing reads, again used for both row tiles; P goes in as
+//     hi + lo bf16 parts (two MFMAs) unless the caller asks for one rounded bf16.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -33,25 +40,30 @@ namespace {
 constexpr int kDqk = 576;                        // key width: latent + rope
 constexpr int kDv = 512;                         // value width: the latent part
 constexpr int kRowB = kDqk * 2;                  // 1152 bytes per cached token
-constexpr int kChunksPerRow = kRowB / 16;        // 72
-constexpr int kBlockChunks = kBlockKeys * kChunksPerRow;   // 1152 16-byte chunks per 16-key block
-constexpr int kLdsBlock = kBlockKeys * kRowB;    // 18 KiB, rows unpadded: chunk slot c of row r holds chunk c ^ (r & 7)
-constexpr int kDmaPerBlock = kLdsBlock / 1024;   // 18 wave-wide loads of 64 x 16 bytes
+constexpr int kMlaKeys = 32;                     // keys per LDS block
+constexpr int kRowChunks = kRowB / 16;           // 72 chunks of 16 bytes per row
+constexpr int kPitchChunks = kRowChunks + 2;     // 74: the pitch in chunks is 2 * odd modulo 16 (see block_to_lds)
+constexpr int kPitch = kPitchChunks * 16;        // 1184 bytes between rows in LDS
+constexpr int kDmaPerBlock = (kMlaKeys * kPitchChunks + 63) / 64;   // 37 wave-wide loads of 64 x 16 bytes
+constexpr int kLdsBlock = kDmaPerBlock * 1024;   // 37888 bytes (the last row's pad is not inside)
+constexpr int kTileB = 16 * kPitch;              // from key tile 0 to key tile 1 of a block
 constexpr int kQSteps = kDqk / 32;               // 18 MFMA steps of 32 columns
-constexpr int kVGroups = kDv / 128;              // 4 groups of 128 value columns
+constexpr int kQRegSteps = 9;                    // Q columns 0 .. 32 * 9 - 1 stay in registers, the rest of Q in LDS
+constexpr int kQLdsWave = (kQSteps - kQRegSteps) * 1024;   // per 16-row tile: one 16-byte chunk per lane and step
+constexpr int kQAhead = 3;                       // key fragments in flight ahead of the MFMAs, in steps
+constexpr int kVAhead = 2;                       // value fragments in flight ahead of the MFMAs, in tile pairs
+constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
 constexpr int kOutPitch = 128 * 4 + 16;          // epilogue: 16 rows x 128 fp32 columns, padded
 constexpr int kLdsOutPerWave = 16 * kOutPitch;
-constexpr int kMaxWaves = 8;
 
-// Running state of one 16-row tile.
+typedef short s16x4v_t __attribute__((ext_vector_type(4)));
+
+// Running state of one 16-row tile.  Lane (kb, n) holds row n.
 struct MlaTile {
-    f32x4_t o[kVGroups * 8];   // o[g * 8 + e][j]: column 128 g + 8 (4 kb + j) + e of row n
-    float m, l;
+    f32x4_t o[kColTiles];      // o[ct][i]: column 16 ct + 4 kb + i
+    float m, l;                // running maximum (log2 domain) and this lane's share of the sum
 };
 
-// This wave's share of the loads of one 16-key block into LDS: load q fills LDS bytes
-// [q * 1024, (q + 1) * 1024) of the block in lane order, i.e. linear chunk position P = 64 q + lane
-// = (row, slot); the lane fetches the global chunk that belongs there, slot ^ (row & 7) of that row.
 // The loads are written as assembly so that the compiler does not order them against LDS reads: it
 // cannot tell the two halves of the double buffer apart and would wait for every outstanding load
 // before each read.  dma_wait() before the workgroup barrier is what makes a block visible.
@@ -61,6 +73,10 @@ __device__ __forceinline__ void dma16(u32x4_t rsrc, uint32_t lds_addr, uint32_t 
 }
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// This wave's share of the loads of one 32-key block into LDS: load q fills LDS bytes
+// [q * 1024, (q + 1) * 1024) of the block in lane order, i.e. chunk position 64 q + lane = 74 row +
+// slot; the lane fetches chunk `slot` of that row (bytes past the sequence's end read as zero), pad
+// positions and positions past row 31 fetch nothing.
 template <int NW>
 __device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_block, int wave, int lane) {
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
@@ -69,114 +85,189 @@ __device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_
         const int qq = wave + q * NW;            // wave-uniform
         if (qq < kDmaPerBlock) {
             const int pos = qq * 64 + lane;
-            const int row = pos / kChunksPerRow, slot = pos - row * kChunksPerRow;
-            const uint32_t voff = (uint32_t)(row * kChunksPerRow + (slot ^ (row & 7))) * 16;
-            dma16(rc, lds0 + qq * 1024, voff, (uint32_t)j_block * kRowB);
+            const int row = pos / kPitchChunks, slot = pos - row * kPitchChunks;
+            if (slot < kRowChunks && row < kMlaKeys)
+                dma16(rc, lds0 + qq * 1024, (uint32_t)(row * kRowB + slot * 16), (uint32_t)j_block * kRowB);
         }
     }
 }
 
-// One 16-key block from LDS against this wave's RT tiles of 16 rows.  Every operand read from LDS (a
-// key fragment, a value fragment) is used for all RT tiles.  kHiLo: the softmax weights go into the
-// value product as hi + lo bf16 parts (two MFMAs, 16 significant bits) instead of one rounded bf16.
+// max / sum over the four lanes (kb = 0..3) that hold the same row: lane-swap instructions, no LDS.
+// The swap exchanges, between its two register operands, lane group 1 (3) of the first with lane
+// group 0 (2) of the second (16-lane form), or the upper half of the first with the lower half of
+// the second (32-lane form): called on (x, x), the two results together hold both partners' values.
+// (The results are copied to scalars before the bit cast: a bit cast applied directly to an element
+// of the result vector read element 0 for both.)
+__device__ __forceinline__ void swap16(float x, float& r0, float& r1) {
+    const uint32_t a = __builtin_bit_cast(uint32_t, x);
+    const u32x2_t t = __builtin_amdgcn_permlane16_swap(a, a, false, false);
+    const uint32_t t0 = t.x, t1 = t.y;
+    r0 = __builtin_bit_cast(float, t0);
+    r1 = __builtin_bit_cast(float, t1);
+}
+__device__ __forceinline__ void swap32(float x, float& r0, float& r1) {
+    const uint32_t a = __builtin_bit_cast(uint32_t, x);
+    const u32x2_t t = __builtin_amdgcn_permlane32_swap(a, a, false, false);
+    const uint32_t t0 = t.x, t1 = t.y;
+    r0 = __builtin_bit_cast(float, t0);
+    r1 = __builtin_bit_cast(float, t1);
+}
+__device__ __forceinline__ float kb_max(float x) {
+    float a, b;
+    swap16(x, a, b);
+    x = fmaxf(a, b);
+    swap32(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float kb_sum(float x) {
+    float a, b;
+    swap16(x, a, b);
+    x = a + b;
+    swap32(x, a, b);
+    return a + b;
+}
+
+// Scheduling groups (the group sizes must be compile-time constants, hence the templates).
+template <int N> __device__ __forceinline__ void sched_ds() { __builtin_amdgcn_sched_group_barrier(0x100, N, 0); }
+template <int N> __device__ __forceinline__ void sched_mfma() { __builtin_amdgcn_sched_group_barrier(0x008, N, 0); }
+constexpr int qk_reads_of(int step, int rt) { return 2 + (step >= kQRegSteps ? rt : 0); }
+constexpr int qk_reads_before(int steps, int rt) {
+    int n = 0;
+    for (int i = 0; i < steps; ++i) n += qk_reads_of(i, rt);
+    return n;
+}
+template <int STEP, int RT>
+struct QkSched {
+    static __device__ __forceinline__ void run() {
+        sched_mfma<2 * RT>();
+        if constexpr (STEP + kQAhead < kQSteps) sched_ds<qk_reads_of(STEP + kQAhead, RT)>();
+        if constexpr (STEP + 1 < kQSteps) QkSched<STEP + 1, RT>::run();
+    }
+};
+
+// One 32-key block from LDS against this wave's RT tiles of 16 rows.  Every operand read from LDS is
+// used for all RT tiles.  kHiLo: the softmax weights go into the value product as hi + lo bf16 parts
+// (two MFMAs, 16 significant bits) instead of one rounded bf16.
+//   qk_base = block + n * kPitch + kb * 16                     (key row n of a tile, chunk kb)
+//   pv_base = block + (4 kb + n / 4) * kPitch + (n % 4) * 8    (transposing read, see below)
 template <int RT, bool kHiLo>
-__device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* lds_block,
-                                          const bf16x8_t (&qop)[RT][kQSteps], float scale_log2, int j_block,
-                                          const int (&lim)[RT], int kb, int n) {
-    // Key n, chunk 4 * step + kb sits in slot (4 * step + kb) ^ (n & 7): the XOR touches the low three
-    // bits only, which alternate between kb and 4 + kb with the step's parity.
-    const char* arow = lds_block + n * kRowB;
-    const int a_even = (kb ^ (n & 7)) * 16, a_odd = ((4 + kb) ^ (n & 7)) * 16;
-    f32x4_t s0[RT], s1[RT];
+__device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base, const char* pv_base,
+                                          const bf16x8_t (&qop)[RT][kQRegSteps], const char* q_lds, float scale_log2,
+                                          int j_block, const int (&lim)[RT], int kb) {
+    // S^T tile kt: A = keys 16 kt .. 16 kt + 15 of the block (lane (kb, n): key n, columns 32 step +
+    // 8 kb .. + 7), B = Q; the result at lane (kb, n) is key 16 kt + 4 kb + i against row n.
+    f32x4_t s[RT][2];
 #pragma unroll
-    for (int rt = 0; rt < RT; ++rt) s0[rt] = s1[rt] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int rt = 0; rt < RT; ++rt) s[rt][0] = s[rt][1] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    // The key fragments (and, from step kQRegSteps on, the lane's Q chunks, which it parked in LDS at
+    // q_lds + tile * kQLdsWave + (step - kQRegSteps) * 1024) are fetched kQAhead steps before the MFMAs
+    // that use them.
+    bf16x8_t ka[kQSteps][2], ql[RT][kQSteps - kQRegSteps];
+    auto load_step = [&](int step) {
+        ka[step][0] = *reinterpret_cast<const bf16x8_t*>(qk_base + step * 64);
+        ka[step][1] = *reinterpret_cast<const bf16x8_t*>(qk_base + kTileB + step * 64);
+        if (step >= kQRegSteps) {
 #pragma unroll
-    for (int step = 0; step < kQSteps; step += 2) {
-        const bf16x8_t a0 = *reinterpret_cast<const bf16x8_t*>(arow + a_even + (step >> 1) * 128);
-        const bf16x8_t a1 = *reinterpret_cast<const bf16x8_t*>(arow + a_odd + (step >> 1) * 128);
+            for (int rt = 0; rt < RT; ++rt)
+                ql[rt][step - kQRegSteps] = *reinterpret_cast<const bf16x8_t*>(q_lds + rt * kQLdsWave + (step - kQRegSteps) * 1024);
+        }
+    };
+#pragma unroll
+    for (int step = 0; step < kQAhead; ++step) load_step(step);
+#pragma unroll
+    for (int step = 0; step < kQSteps; ++step) {
+        if (step + kQAhead < kQSteps) load_step(step + kQAhead);
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            s0[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, qop[rt][step], s0[rt], 0, 0, 0);
-            s1[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, qop[rt][step + 1], s1[rt], 0, 0, 0);
+            const bf16x8_t qv = step < kQRegSteps ? qop[rt][step < kQRegSteps ? step : 0] : ql[rt][step < kQRegSteps ? 0 : step - kQRegSteps];
+            s[rt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[step][0], qv, s[rt][0], 0, 0, 0);
+            s[rt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[step][1], qv, s[rt][1], 0, 0, 0);
         }
     }
-    u32x2_t ph[RT], pl[RT];
+    // Pin that order for the instruction scheduler: the first reads, then MFMAs and reads in turn.
+    sched_ds<qk_reads_before(kQAhead, RT)>();
+    QkSched<0, RT>::run();
+    // O^T tile ct: A = value columns 16 ct .. + 15 (lane (kb, n): column n, keys as in the softmax
+    // below), B = P^T.  A transposing read hands lane n of a 16-lane group, from the 64 values that
+    // the group's lanes point at taken in lane order, the values n, n + 16, n + 32, n + 48: lanes 4 j ..
+    // 4 j + 3 point at 16 consecutive columns of key 4 kb + j, so lane n receives column n of keys
+    // 4 kb .. 4 kb + 3.  The first value fragments are fetched here, ahead of the softmax.
+    bf16x8_t va[kColTiles];
+    auto load_v = [&](int ct) {
+        const s16x4v_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4v_t*)(pv_base + ct * 32));
+        const s16x4v_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4v_t*)(pv_base + kTileB + ct * 32));
+        const u32x2_t w0 = __builtin_bit_cast(u32x2_t, v0), w1 = __builtin_bit_cast(u32x2_t, v1);
+        return __builtin_bit_cast(bf16x8_t, u32x4_t{w0.x, w0.y, w1.x, w1.y});
+    };
+#pragma unroll
+    for (int ct = 0; ct < 2 * kVAhead; ++ct) va[ct] = load_v(ct);
+    // Softmax.  The lane's 8 weights of a row, ordered (kt, i), are the B operand of the value product
+    // when contraction index 8 kb + 4 kt + i stands for key 16 kt + 4 kb + i.
+    bf16x8_t ph[RT], pl[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
-        const f32x4_t s = s0[rt] + s1[rt];      // s[i] = score of key j_block + 4*kb + i for row n of tile rt
-        float p[4];
+        float p[8];
         float mx = kNegInf;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] = (j_block + 4 * kb + i < lim[rt]) ? s[i] * scale_log2 : kNegInf;
-            mx = fmaxf(mx, p[i]);
+        for (int t = 0; t < 8; ++t) {
+            const int key = j_block + 16 * (t >> 2) + 4 * kb + (t & 3);
+            p[t] = key < lim[rt] ? s[rt][t >> 2][t & 3] * scale_log2 : kNegInf;
+            mx = fmaxf(mx, p[t]);
         }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = kb_max(mx);
         const float m_new = fmaxf(st[rt].m, mx);
         const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
         const float alpha = fast_exp2(st[rt].m - m_use);
         float sum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i] = fast_exp2(p[i] - m_use);
-            sum += p[i];
+        for (int t = 0; t < 8; ++t) {
+            p[t] = fast_exp2(p[t] - m_use);
+            sum += p[t];
         }
         st[rt].l = st[rt].l * alpha + sum;
         st[rt].m = m_new;
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-            for (int t = 0; t < kVGroups * 8; ++t) st[rt].o[t] *= alpha;
+            for (int ct = 0; ct < kColTiles; ++ct) st[rt].o[ct] *= alpha;
         }
-        const f32x2_t p01 = {p[0], p[1]}, p23 = {p[2], p[3]};
-        const bf16x2_t h01 = __builtin_convertvector(p01, bf16x2_t), h23 = __builtin_convertvector(p23, bf16x2_t);
-        ph[rt] = u32x2_t{__builtin_bit_cast(uint32_t, h01), __builtin_bit_cast(uint32_t, h23)};
-        pl[rt] = u32x2_t{0u, 0u};
-        if (kHiLo) {
-            const f32x2_t r01 = p01 - __builtin_convertvector(h01, f32x2_t);
-            const f32x2_t r23 = p23 - __builtin_convertvector(h23, f32x2_t);
-            pl[rt] = u32x2_t{__builtin_bit_cast(uint32_t, __builtin_convertvector(r01, bf16x2_t)),
-                             __builtin_bit_cast(uint32_t, __builtin_convertvector(r23, bf16x2_t))};
+        uint32_t h[4], lo[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const f32x2_t pp = {p[2 * u], p[2 * u + 1]};
+            const bf16x2_t hh = __builtin_convertvector(pp, bf16x2_t);
+            h[u] = __builtin_bit_cast(uint32_t, hh);
+            if (kHiLo) lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp - __builtin_convertvector(hh, f32x2_t), bf16x2_t));
         }
+        ph[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{h[0], h[1], h[2], h[3]});
+        pl[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
     }
-    // Values: lane (kb, x) reads, for keys 4 kb + i, chunk 16 g + x (columns 128 g + 8 x .. + 7), which
-    // sits in slot 16 g + (x ^ (key & 7)); half a chunk (4 columns, 64 bits) at a time to keep the
-    // live registers down.  Column tile e of the group takes the e-th bf16 of the four keys' chunks.
-    int vaddr[4];
+    // Value product, fragments kVAhead tile pairs ahead; per pair the hi parts of both tiles (and row
+    // tiles) first, then the lo parts, so that no MFMA waits for the one just before it.
 #pragma unroll
-    for (int i = 0; i < 4; ++i) vaddr[i] = (4 * kb + i) * kRowB + ((n ^ ((4 * kb + i) & 7)) * 16);
+    for (int c2 = 0; c2 < kColTiles; c2 += 2) {
+        if (c2 + 2 * kVAhead < kColTiles) {
+            va[c2 + 2 * kVAhead] = load_v(c2 + 2 * kVAhead);
+            va[c2 + 2 * kVAhead + 1] = load_v(c2 + 2 * kVAhead + 1);
+        }
 #pragma unroll
-    for (int g = 0; g < kVGroups; ++g) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            u32x2_t v[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = *reinterpret_cast<const u32x2_t*>(lds_block + vaddr[i] + g * 256 + h * 8);
-            u32x2_t a[4];
-#pragma unroll
-            for (int e2 = 0; e2 < 4; ++e2) {
-                const uint32_t sel = (e2 & 1) ? 0x07060302u : 0x05040100u;
-                a[e2] = u32x2_t{__builtin_amdgcn_perm(v[1][e2 >> 1], v[0][e2 >> 1], sel),
-                                __builtin_amdgcn_perm(v[3][e2 >> 1], v[2][e2 >> 1], sel)};
-            }
-            // independent accumulators back to back; the lo parts follow once all hi parts are issued
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
+                st[rt].o[c2 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c2 + u], ph[rt], st[rt].o[c2 + u], 0, 0, 0);
+        if (kHiLo) {
 #pragma unroll
-                for (int e2 = 0; e2 < 4; ++e2)
-                    st[rt].o[g * 8 + 4 * h + e2] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                        __builtin_bit_cast(s16x4_t, a[e2]), __builtin_bit_cast(s16x4_t, ph[rt]),
-                        st[rt].o[g * 8 + 4 * h + e2], 0, 0, 0);
-            if (kHiLo) {
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-                    for (int e2 = 0; e2 < 4; ++e2)
-                        st[rt].o[g * 8 + 4 * h + e2] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-                            __builtin_bit_cast(s16x4_t, a[e2]), __builtin_bit_cast(s16x4_t, pl[rt]),
-                            st[rt].o[g * 8 + 4 * h + e2], 0, 0, 0);
-            }
+                    st[rt].o[c2 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c2 + u], pl[rt], st[rt].o[c2 + u], 0, 0, 0);
         }
+    }
+#pragma unroll
+    for (int c2 = 0; c2 < kColTiles; c2 += 2) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * RT * (kHiLo ? 2 : 1), 0);
+        if (c2 + 2 * kVAhead < kColTiles) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
     }
 }
 
@@ -185,7 +276,10 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* lds_blo
 template <int NW, int RT, bool kHiLo>
 __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     __shared__ __attribute__((aligned(16))) char lds_c[2 * kLdsBlock];
-    __shared__ __attribute__((aligned(16))) char lds_out[NW * kLdsOutPerWave];
+    // Per wave and tile: the Q chunks of steps kQRegSteps.. (each lane reads back what it wrote); the
+    // same bytes stage the output at the end of a segment, when Q is no longer needed.
+    __shared__ __attribute__((aligned(16))) char lds_q[NW * RT * kQLdsWave];
+    static_assert(kQLdsWave >= kLdsOutPerWave, "output staging must fit the wave's Q area");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 4, n = lane & 15;
     const int T = prm.q_len, H = prm.n_heads, rows_total = T * H;
@@ -236,7 +330,10 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
 
     // Row n of tile rt of this wave: row index within the sequence's T * H rows.
     const int wave_row0 = blockIdx.y * (16 * RT * NW) + wave * (16 * RT);
-    char* out_lds = lds_out + wave * kLdsOutPerWave;
+    char* q_lds = lds_q + wave * (RT * kQLdsWave) + lane * 16;
+    char* out_lds = lds_q + wave * (RT * kQLdsWave);
+    const int qk_off = n * kPitch + kb * 16;
+    const int pv_off = (4 * kb + (n >> 2)) * kPitch + (n & 3) * 8;
     auto fence = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -259,8 +356,8 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                             cbytes > 0xffffffffull ? 0xffffffffu : (uint32_t)cbytes, 0x00020000u};
 
         block_to_lds<NW>(lds_c, rc, j0, wave, lane);        // block 0 -> buffer 0
-        // Q operand: lane (kb, n) holds chunk 4 * step + kb of row n of each tile.
-        bf16x8_t qop[RT][kQSteps];
+        // Q operand: lane (kb, n) holds columns 32 step + 8 kb .. + 7 of row n of each tile.
+        bf16x8_t qop[RT][kQRegSteps];
         int lim[RT];
         MlaTile st[RT];
 #pragma unroll
@@ -272,46 +369,50 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
             for (int step = 0; step < kQSteps; ++step) {
                 u32x4_t qv = {0u, 0u, 0u, 0u};
                 if (row_ok) qv = *reinterpret_cast<const u32x4_t*>(prm.q + qrow * kDqk + (4 * step + kb) * 8);
-                qop[rt][step] = __builtin_bit_cast(bf16x8_t, qv);
+                if (step < kQRegSteps) qop[rt][step < kQRegSteps ? step : 0] = __builtin_bit_cast(bf16x8_t, qv);
+                else *reinterpret_cast<u32x4_t*>(q_lds + rt * kQLdsWave + (step - kQRegSteps) * 1024) = qv;
             }
             const int causal = L - T + (row_ok ? row : 0) / H + 1;
             lim[rt] = causal < j1 ? causal : j1;
 #pragma unroll
-            for (int i = 0; i < kVGroups * 8; ++i) st[rt].o[i] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+            for (int ct = 0; ct < kColTiles; ++ct) st[rt].o[ct] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
             st[rt].m = kNegInf;
             st[rt].l = 0.0f;
         }
 
-        const int n_blocks = (j1 - j0 + kBlockKeys - 1) / kBlockKeys;
+        // Q is used here, before the loop, so that the wait for its loads sits here as well: a wait
+        // inside the loop would also wait for the block loads that were just issued.
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int step = 0; step < kQRegSteps; ++step) asm volatile("" : "+v"(qop[rt][step]));
+        fence();                  // the Q chunks in LDS are read back by the lane that wrote them
+
+        const int n_blocks = (j1 - j0 + kMlaKeys - 1) / kMlaKeys;
         for (int blk = 0; blk < n_blocks; ++blk) {
-            char* cur = lds_c + (blk & 1) * kLdsBlock;
+            const char* cur = lds_c + (blk & 1) * kLdsBlock;
             // Every wave waits for its own loads of block blk, then the barrier: block blk is in LDS
             // and everyone is done reading block blk - 1, whose buffer the next loads may overwrite.
             dma_wait();
             __syncthreads();
             if (blk + 1 < n_blocks)
-                block_to_lds<NW>(lds_c + ((blk + 1) & 1) * kLdsBlock, rc, j0 + (blk + 1) * kBlockKeys, wave, lane);
-            mla_block<RT, kHiLo>(st, cur, qop, prm.scale_log2, j0 + blk * kBlockKeys, lim, kb, n);
+                block_to_lds<NW>(lds_c + ((blk + 1) & 1) * kLdsBlock, rc, j0 + (blk + 1) * kMlaKeys, wave, lane);
+            mla_block<RT, kHiLo>(st, cur + qk_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb);
         }
         __syncthreads();          // the next segment's first block reuses buffer 0
 
         // Store, 128 columns at a time through this wave's LDS so that stores write whole rows.
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            float l = st[rt].l;
-            l += __shfl_xor(l, 16, 64);
-            l += __shfl_xor(l, 32, 64);
+            const float l = kb_sum(st[rt].l);
             const float sc = whole ? (l > 0.0f ? 1.0f / l : 0.0f) : 1.0f;
             const int tile_row0 = wave_row0 + 16 * rt;
 #pragma unroll
-            for (int g = 0; g < kVGroups; ++g) {
+            for (int g = 0; g < kDv / 128; ++g) {
 #pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    float4* w = reinterpret_cast<float4*>(out_lds + n * kOutPitch + (4 * kb + jj) * 32);
-                    w[0] = make_float4(st[rt].o[g * 8 + 0][jj] * sc, st[rt].o[g * 8 + 1][jj] * sc,
-                                       st[rt].o[g * 8 + 2][jj] * sc, st[rt].o[g * 8 + 3][jj] * sc);
-                    w[1] = make_float4(st[rt].o[g * 8 + 4][jj] * sc, st[rt].o[g * 8 + 5][jj] * sc,
-                                       st[rt].o[g * 8 + 6][jj] * sc, st[rt].o[g * 8 + 7][jj] * sc);
+                for (int c = 0; c < 8; ++c) {
+                    const f32x4_t o = st[rt].o[8 * g + c] * sc;
+                    *reinterpret_cast<float4*>(out_lds + n * kOutPitch + (16 * c + 4 * kb) * 4) = make_float4(o[0], o[1], o[2], o[3]);
                 }
                 fence();
 #pragma unroll
@@ -415,13 +516,13 @@ hipError_t launch_mla_cfg(const MlaParams& prm, dim3 grid, hipStream_t stream) {
 }  // namespace
 
 // Workgroup shape for rows_total = q_len * n_heads query rows per sequence: (waves, 16-row tiles per
-// wave).  layout 1 forces one tile per wave (up to 8 waves), layout 2 two tiles per wave (4 waves).
+// wave).  Automatic: one tile per wave, 8 waves from 65 rows on (two waves per SIMD, 256 registers
+// each).  layout 1: at most 4 waves of one tile (64 rows per workgroup); layout 2: 4 waves of two
+// tiles from 65 rows on (one wave per SIMD; its accumulators do not fit the register file and spill).
 void mla_block_shape(int rows_total, int layout, int* waves, int* tiles_per_wave) {
     const int tiles = (rows_total + 15) / 16;
-    if (tiles >= 8 && layout == 2) { *waves = 4; *tiles_per_wave = 2; return; }
-    *tiles_per_wave = 1;
-    if (layout == 3 && tiles >= 4) { *waves = 4; return; }
-    *waves = tiles >= 8 ? 8 : tiles >= 4 ? 4 : tiles >= 2 ? 2 : 1;
+    *tiles_per_wave = (tiles > 4 && layout == 2) ? 2 : 1;
+    *waves = (layout != 1 && layout != 2 && tiles > 4) ? 8 : tiles >= 3 ? 4 : tiles;
 }
 
 hipError_t launch_mla_decode(const MlaParams& prm, hipStream_t stream, hipEvent_t* events) {
