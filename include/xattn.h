@@ -95,6 +95,7 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
  * c_ptrs  DEVICE array[batch] of DEVICE pointers; c_ptrs[b] -> bf16 [>= kv_lens[b], d_latent + d_rope],
  *         16-byte aligned; an xTensor range or any other device memory
  * kv_lens DEVICE int32[batch], as for xattn_decode
+ * scale   positive and finite (XATTN_EINVAL otherwise)
  * out     DEVICE bf16 [batch, q_len, n_heads, d_latent];  lse DEVICE fp32 [batch, q_len, n_heads] or NULL
  * Supported: d_latent = 512, d_rope = 64, q_len * n_heads <= 4096, batch <= 4096; otherwise
  * XATTN_EUNSUPPORTED.  Same partition, workspace, stream, capture and ownership rules as xattn_decode.

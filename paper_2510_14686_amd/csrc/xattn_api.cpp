@@ -296,7 +296,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     if (batch > kMaxBatch) return fail(XATTN_EUNSUPPORTED, "batch %d exceeds %d", batch, kMaxBatch);
     if (q_len > kMaxQLen) return fail(XATTN_EUNSUPPORTED, "q_len %d exceeds %d", q_len, kMaxQLen);
     if ((long)q_len * n_heads > 4096) return fail(XATTN_EUNSUPPORTED, "q_len * n_heads = %ld exceeds 4096", (long)q_len * n_heads);
-    if (!std::isfinite(scale)) return fail(XATTN_EINVAL, "xattn_mla_decode: scale is not finite");
+    if (!std::isfinite(scale) || !(scale > 0.0f)) return fail(XATTN_EINVAL, "xattn_mla_decode: scale %g is not a positive finite number", (double)scale);
     if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
         return fail(XATTN_EINVAL, "xattn_mla_decode: q and out must be 16-byte aligned");
 
@@ -305,11 +305,11 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     int st = device_state(&d, nullptr);
     if (st != XATTN_OK) return st;
     const int n_pieces = pieces_for(d->n_cu);
-    // same layout as the GQA path: per-sequence table, partial (m, l), partial rows of 512 fp32
+    // per-sequence table, partial (m, l, lq) per row, partial rows of 512 fp32
     const size_t slots = (size_t)n_pieces + (size_t)batch;
     const size_t rows = (size_t)q_len * (size_t)n_heads;
     const size_t ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
-    const size_t o_off = ml_off + align_up(slots * rows * 2 * sizeof(float), 256);
+    const size_t o_off = ml_off + align_up(slots * rows * 4 * sizeof(float), 256);      // (m, l, lq, -) per partial row
     const size_t total = o_off + align_up(slots * rows * 512 * sizeof(float), 256);
     char* ws = nullptr;
     st = acquire_workspace(d, total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);
@@ -332,7 +332,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;
     prm.layout = g_cfg_mla_layout;
-    prm.hi_lo = g_cfg_pv_mode == 2 ? 0 : 1;       // XATTN_CFG_PV_MODE 2 rounds the weights to one bf16
+    prm.hi_lo = g_cfg_pv_mode == 1 ? 1 : 0;       // XATTN_CFG_PV_MODE 1: weights as hi + lo bf16 parts
     hipEvent_t* events = nullptr;
     st = timing_events(&events);
     if (st != XATTN_OK) return st;

@@ -16,10 +16,9 @@
 //   * the block (32 x 1152 bytes, contiguous in memory) goes from HBM straight into LDS (buffer loads
 //     with the LDS destination, 1 KiB per wave instruction, no staging registers), once per
 //     workgroup, two LDS buffers, one barrier per block, the next block in flight during the
-//     arithmetic.  Rows sit 1184 bytes apart in LDS (two 16-byte pad chunks; the pad is made through
-//     the global address each lane fetches, since the LDS side of such a load is fixed to lane order):
-//     measured, a pitch of 2 * odd chunks modulo 16 serves both read patterns below without bank
-//     conflicts, an odd pitch (1168) halves the rate of both;
+//     arithmetic.  In LDS the latent and the rope part of the rows sit in two areas with padded
+//     pitches chosen against bank conflicts (the LDS side of such a load is fixed to lane order, so
+//     the layout is made through the global address each lane fetches);
 //   * S^T = C Q^T: per 16-key tile 18 bf16 MFMA 16x16x32, the A operand (keys) read from LDS and used
 //     for both row tiles of the wave;
 //   * softmax on the accumulator layout: lane (kb, n) holds, of row n, the keys 4 kb + i of both key
@@ -41,20 +40,30 @@ constexpr int kDqk = 576;                        // key width: latent + rope
 constexpr int kDv = 512;                         // value width: the latent part
 constexpr int kRowB = kDqk * 2;                  // 1152 bytes per cached token
 constexpr int kMlaKeys = 32;                     // keys per LDS block
-constexpr int kRowChunks = kRowB / 16;           // 72 chunks of 16 bytes per row
-constexpr int kPitchChunks = kRowChunks + 2;     // 74: the pitch in chunks is 2 * odd modulo 16 (see block_to_lds)
-constexpr int kPitch = kPitchChunks * 16;        // 1184 bytes between rows in LDS
-constexpr int kDmaPerBlock = (kMlaKeys * kPitchChunks + 63) / 64;   // 37 wave-wide loads of 64 x 16 bytes
-constexpr int kLdsBlock = kDmaPerBlock * 1024;   // 37888 bytes (the last row's pad is not inside)
+// LDS image of a block: the first 1024 bytes of each row (the latent part, 64 chunks of 16 bytes) at
+// pitch kPitch, the last 128 bytes (the rope part) in a tail area at pitch kTailPitch.  Both pitches are
+// 2 * odd chunks modulo 16: measured, that serves the operand reads below without bank conflicts (an
+// odd pitch halves their rate).
+constexpr int kPitch = 1024 + 32;                // 1056
+constexpr int kTailPitch = 128 + 32;             // 160
+constexpr int kTailRowsPerLoad = 6;              // one wave-wide load fills the tails of 6 rows (60 lanes)
+constexpr int kTailLoads = (kMlaKeys + kTailRowsPerLoad - 1) / kTailRowsPerLoad;          // 6
+constexpr int kTailOff = kMlaKeys * kPitch;      // 33792: start of the tail area
+constexpr int kLdsBlock = kTailOff + (kTailLoads - 1) * kTailRowsPerLoad * kTailPitch + 1024;   // 39616
+constexpr int kDmaPerBlock = kMlaKeys + kTailLoads;   // 38 wave-wide loads of 64 x 16 bytes
 constexpr int kTileB = 16 * kPitch;              // from key tile 0 to key tile 1 of a block
+constexpr int kTailTileB = 16 * kTailPitch;
+constexpr int kMainSteps = 1024 / 64;            // MFMA steps 0..15 read the latent part, 16..17 the tail
 constexpr int kQSteps = kDqk / 32;               // 18 MFMA steps of 32 columns
-constexpr int kQRegSteps = 9;                    // Q columns 0 .. 32 * 9 - 1 stay in registers, the rest of Q in LDS
+constexpr int kQRegSteps = 13;                   // Q columns 0 .. 32 * 9 - 1 stay in registers, the rest of Q in LDS
 constexpr int kQLdsWave = (kQSteps - kQRegSteps) * 1024;   // per 16-row tile: one 16-byte chunk per lane and step
-constexpr int kQAhead = 3;                       // key fragments in flight ahead of the MFMAs, in steps
-constexpr int kVAhead = 2;                       // value fragments in flight ahead of the MFMAs, in tile pairs
+constexpr int kQAhead = 2;                       // key fragments in flight ahead of the MFMAs, in steps
+constexpr int kVAhead = 1;                       // value fragments in flight ahead of the MFMAs, in tile pairs
 constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
-constexpr int kOutPitch = 128 * 4 + 16;          // epilogue: 16 rows x 128 fp32 columns, padded
+constexpr int kOutCols = 64;                     // epilogue: 16 rows x 64 fp32 columns at a time, padded
+constexpr int kOutPitch = kOutCols * 4 + 16;
 constexpr int kLdsOutPerWave = 16 * kOutPitch;
+constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
 
@@ -62,6 +71,7 @@ typedef short s16x4v_t __attribute__((ext_vector_type(4)));
 struct MlaTile {
     f32x4_t o[kColTiles];      // o[ct][i]: column 16 ct + 4 kb + i
     float m, l;                // running maximum (log2 domain) and this lane's share of the sum
+    float lq;                  // the same sum over the weights as they enter the value product
 };
 
 // The loads are written as assembly so that the compiler does not order them against LDS reads: it
@@ -71,23 +81,52 @@ __device__ __forceinline__ void dma16(u32x4_t rsrc, uint32_t lds_addr, uint32_t 
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 1\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
                  :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
-__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Waits until at most n of this wave's loads are outstanding (they complete in order): n = the number
+// of loads of the newest block leaves the block before it complete.
+__device__ __forceinline__ void dma_wait(int n) {
+    switch (n) {           // n is wave-uniform; the instruction takes an immediate
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+        case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+        case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+        case 19: asm volatile("s_waitcnt vmcnt(19)" ::: "memory"); break;
+        case 38: asm volatile("s_waitcnt vmcnt(38)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+}
 
-// This wave's share of the loads of one 32-key block into LDS: load q fills LDS bytes
-// [q * 1024, (q + 1) * 1024) of the block in lane order, i.e. chunk position 64 q + lane = 74 row +
-// slot; the lane fetches chunk `slot` of that row (bytes past the sequence's end read as zero), pad
-// positions and positions past row 31 fetch nothing.
+// This wave's share of the loads of one 32-key block into LDS.  A load fills 1024 consecutive LDS
+// bytes in lane order.  Load r < 32: the latent part of row r, lane l fetching chunk l.  Load 32 + p:
+// the tails of rows 6 p .. 6 p + 5, lane l = 10 i + c fetching chunk 64 + c of row 6 p + i (c < 8;
+// lanes with c >= 8, l >= 60 or a row past the block fetch nothing).  Bytes past the sequence's end
+// read as zero.  The per-lane parts of the addresses (dma.main_off, dma.tail_off) do not depend on
+// the load, the rest is scalar.
+struct DmaLane {
+    uint32_t main_off, tail_off;
+    int tail_row;                // 6 p + tail_row is the lane's row in a tail load; 64 for lanes that fetch nothing
+};
+__device__ __forceinline__ DmaLane dma_lane(int lane) {
+    DmaLane d;
+    const int i = lane / 10, c = lane - 10 * i;
+    d.main_off = (uint32_t)lane * 16;
+    d.tail_off = (uint32_t)(i * kRowB + 1024 + c * 16);
+    d.tail_row = (c < 8 && i < kTailRowsPerLoad) ? i : 64;
+    return d;
+}
 template <int NW>
-__device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_block, int wave, int lane) {
+__device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_block, int wave, const DmaLane& dma) {
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
 #pragma unroll
     for (int q = 0; q < (kDmaPerBlock + NW - 1) / NW; ++q) {
-        const int qq = wave + q * NW;            // wave-uniform
-        if (qq < kDmaPerBlock) {
-            const int pos = qq * 64 + lane;
-            const int row = pos / kPitchChunks, slot = pos - row * kPitchChunks;
-            if (slot < kRowChunks && row < kMlaKeys)
-                dma16(rc, lds0 + qq * 1024, (uint32_t)(row * kRowB + slot * 16), (uint32_t)j_block * kRowB);
+        const int g = wave + q * NW;             // wave-uniform
+        if (g < kMlaKeys) {
+            dma16(rc, lds0 + g * kPitch, dma.main_off, (uint32_t)(j_block + g) * kRowB);
+        } else if (g < kDmaPerBlock) {
+            const int p = g - kMlaKeys;
+            if (p * kTailRowsPerLoad + dma.tail_row < kMlaKeys)
+                dma16(rc, lds0 + kTailOff + p * (kTailRowsPerLoad * kTailPitch), dma.tail_off,
+                      (uint32_t)(j_block + p * kTailRowsPerLoad) * kRowB);
         }
     }
 }
@@ -149,9 +188,10 @@ struct QkSched {
 // used for all RT tiles.  kHiLo: the softmax weights go into the value product as hi + lo bf16 parts
 // (two MFMAs, 16 significant bits) instead of one rounded bf16.
 //   qk_base = block + n * kPitch + kb * 16                     (key row n of a tile, chunk kb)
+//   qt_base = block + kTailOff + n * kTailPitch + kb * 16      (the same for the rope part)
 //   pv_base = block + (4 kb + n / 4) * kPitch + (n % 4) * 8    (transposing read, see below)
 template <int RT, bool kHiLo>
-__device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base, const char* pv_base,
+__device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base, const char* qt_base, const char* pv_base,
                                           const bf16x8_t (&qop)[RT][kQRegSteps], const char* q_lds, float scale_log2,
                                           int j_block, const int (&lim)[RT], int kb) {
     // S^T tile kt: A = keys 16 kt .. 16 kt + 15 of the block (lane (kb, n): key n, columns 32 step +
@@ -164,8 +204,13 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     // that use them.
     bf16x8_t ka[kQSteps][2], ql[RT][kQSteps - kQRegSteps];
     auto load_step = [&](int step) {
-        ka[step][0] = *reinterpret_cast<const bf16x8_t*>(qk_base + step * 64);
-        ka[step][1] = *reinterpret_cast<const bf16x8_t*>(qk_base + kTileB + step * 64);
+        if (step < kMainSteps) {
+            ka[step][0] = *reinterpret_cast<const bf16x8_t*>(qk_base + step * 64);
+            ka[step][1] = *reinterpret_cast<const bf16x8_t*>(qk_base + kTileB + step * 64);
+        } else {
+            ka[step][0] = *reinterpret_cast<const bf16x8_t*>(qt_base + (step - kMainSteps) * 64);
+            ka[step][1] = *reinterpret_cast<const bf16x8_t*>(qt_base + kTailTileB + (step - kMainSteps) * 64);
+        }
         if (step >= kQRegSteps) {
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
@@ -208,22 +253,28 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     bf16x8_t ph[RT], pl[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
+        // Keys at or past lim[rt] (the end of the segment, or the causal limit of the row) count as
+        // -inf; only the blocks that reach that far pay for the comparison.  scale_log2 > 0, so the
+        // maximum is taken before scaling, and one fused multiply-add scales and shifts.
         float p[8];
-        float mx = kNegInf;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            const int key = j_block + 16 * (t >> 2) + 4 * kb + (t & 3);
-            p[t] = key < lim[rt] ? s[rt][t >> 2][t & 3] * scale_log2 : kNegInf;
-            mx = fmaxf(mx, p[t]);
+        for (int t = 0; t < 8; ++t) p[t] = s[rt][t >> 2][t & 3];
+        if (__builtin_amdgcn_ballot_w64(j_block + kMlaKeys > lim[rt]) != 0) {
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                const int key = j_block + 16 * (t >> 2) + 4 * kb + (t & 3);
+                p[t] = key < lim[rt] ? p[t] : kNegInf;
+            }
         }
-        mx = kb_max(mx);
+        float mx = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
+        mx = kb_max(mx) * scale_log2;
         const float m_new = fmaxf(st[rt].m, mx);
         const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
         const float alpha = fast_exp2(st[rt].m - m_use);
         float sum = 0.0f;
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            p[t] = fast_exp2(p[t] - m_use);
+            p[t] = fast_exp2(__builtin_fmaf(p[t], scale_log2, -m_use));
             sum += p[t];
         }
         st[rt].l = st[rt].l * alpha + sum;
@@ -232,14 +283,21 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
 #pragma unroll
             for (int ct = 0; ct < kColTiles; ++ct) st[rt].o[ct] *= alpha;
         }
+        // With one bf16 per weight the output is normalised by the sum of the ROUNDED weights: a
+        // softmax over slightly perturbed scores (relative weight error 2^-9, the same for equal
+        // weights, none for a lone key) instead of rounded weights over an exact sum.
         uint32_t h[4], lo[4] = {0u, 0u, 0u, 0u};
+        float sum_q = 0.0f;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const f32x2_t pp = {p[2 * u], p[2 * u + 1]};
             const bf16x2_t hh = __builtin_convertvector(pp, bf16x2_t);
+            const f32x2_t back = __builtin_convertvector(hh, f32x2_t);
             h[u] = __builtin_bit_cast(uint32_t, hh);
-            if (kHiLo) lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp - __builtin_convertvector(hh, f32x2_t), bf16x2_t));
+            if (kHiLo) lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp - back, bf16x2_t));
+            else sum_q += back[0] + back[1];
         }
+        st[rt].lq = kHiLo ? st[rt].l : st[rt].lq * alpha + sum_q;
         ph[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{h[0], h[1], h[2], h[3]});
         pl[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
     }
@@ -275,7 +333,7 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
 // w * RT .. w * RT + RT - 1 of its group.
 template <int NW, int RT, bool kHiLo>
 __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
-    __shared__ __attribute__((aligned(16))) char lds_c[2 * kLdsBlock];
+    __shared__ __attribute__((aligned(16))) char lds_c[kStages * kLdsBlock];
     // Per wave and tile: the Q chunks of steps kQRegSteps.. (each lane reads back what it wrote); the
     // same bytes stage the output at the end of a segment, when Q is no longer needed.
     __shared__ __attribute__((aligned(16))) char lds_q[NW * RT * kQLdsWave];
@@ -332,7 +390,10 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     const int wave_row0 = blockIdx.y * (16 * RT * NW) + wave * (16 * RT);
     char* q_lds = lds_q + wave * (RT * kQLdsWave) + lane * 16;
     char* out_lds = lds_q + wave * (RT * kQLdsWave);
+    const DmaLane dma = dma_lane(lane);
+    const int my_loads = (kDmaPerBlock - wave + NW - 1) / NW;      // block loads this wave issues per block
     const int qk_off = n * kPitch + kb * 16;
+    const int qt_off = kTailOff + n * kTailPitch + kb * 16;
     const int pv_off = (4 * kb + (n >> 2)) * kPitch + (n & 3) * 8;
     auto fence = [] {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -355,7 +416,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                             (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(caddr >> 32) & 0xffffu)),
                             cbytes > 0xffffffffull ? 0xffffffffu : (uint32_t)cbytes, 0x00020000u};
 
-        block_to_lds<NW>(lds_c, rc, j0, wave, lane);        // block 0 -> buffer 0
+        block_to_lds<NW>(lds_c, rc, j0, wave, dma);        // block 0 -> buffer 0
         // Q operand: lane (kb, n) holds columns 32 step + 8 kb .. + 7 of row n of each tile.
         bf16x8_t qop[RT][kQRegSteps];
         int lim[RT];
@@ -378,6 +439,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
             for (int ct = 0; ct < kColTiles; ++ct) st[rt].o[ct] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
             st[rt].m = kNegInf;
             st[rt].l = 0.0f;
+            st[rt].lq = 0.0f;
         }
 
         // Q is used here, before the loop, so that the wait for its loads sits here as well: a wait
@@ -389,45 +451,51 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         fence();                  // the Q chunks in LDS are read back by the lane that wrote them
 
         const int n_blocks = (j1 - j0 + kMlaKeys - 1) / kMlaKeys;
+        if (n_blocks > 1) block_to_lds<NW>(lds_c + kLdsBlock, rc, j0 + kMlaKeys, wave, dma);   // block 1 -> buffer 1
+        int cur_buf = 0, next_buf = 2;         // block blk sits in buffer blk % 3, block blk + 2 goes to next_buf
         for (int blk = 0; blk < n_blocks; ++blk) {
-            const char* cur = lds_c + (blk & 1) * kLdsBlock;
-            // Every wave waits for its own loads of block blk, then the barrier: block blk is in LDS
-            // and everyone is done reading block blk - 1, whose buffer the next loads may overwrite.
-            dma_wait();
+            const char* cur = lds_c + cur_buf * kLdsBlock;
+            // Every wave waits for its own loads of block blk (those of block blk + 1 may stay in
+            // flight), then the barrier: block blk is in LDS and everyone is done reading block
+            // blk - 1, whose buffer the loads of block blk + 2 may overwrite.
+            dma_wait(blk + 1 < n_blocks ? my_loads : 0);
             __syncthreads();
-            if (blk + 1 < n_blocks)
-                block_to_lds<NW>(lds_c + ((blk + 1) & 1) * kLdsBlock, rc, j0 + (blk + 1) * kMlaKeys, wave, lane);
-            mla_block<RT, kHiLo>(st, cur + qk_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb);
+            if (blk + 2 < n_blocks)
+                block_to_lds<NW>(lds_c + next_buf * kLdsBlock, rc, j0 + (blk + 2) * kMlaKeys, wave, dma);
+            mla_block<RT, kHiLo>(st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb);
+            cur_buf = cur_buf == kStages - 1 ? 0 : cur_buf + 1;
+            next_buf = next_buf == kStages - 1 ? 0 : next_buf + 1;
         }
         __syncthreads();          // the next segment's first block reuses buffer 0
 
-        // Store, 128 columns at a time through this wave's LDS so that stores write whole rows.
+        // Store, 64 columns at a time through this wave's LDS so that a store instruction writes whole
+        // 256-byte pieces of rows.
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const float l = kb_sum(st[rt].l);
-            const float sc = whole ? (l > 0.0f ? 1.0f / l : 0.0f) : 1.0f;
+            const float lq = kHiLo ? l : kb_sum(st[rt].lq);
+            const float sc = whole ? (lq > 0.0f ? 1.0f / lq : 0.0f) : 1.0f;
             const int tile_row0 = wave_row0 + 16 * rt;
 #pragma unroll
-            for (int g = 0; g < kDv / 128; ++g) {
+            for (int g = 0; g < kDv / kOutCols; ++g) {
 #pragma unroll
-                for (int c = 0; c < 8; ++c) {
-                    const f32x4_t o = st[rt].o[8 * g + c] * sc;
+                for (int c = 0; c < kOutCols / 16; ++c) {
+                    const f32x4_t o = st[rt].o[(kOutCols / 16) * g + c] * sc;
                     *reinterpret_cast<float4*>(out_lds + n * kOutPitch + (16 * c + 4 * kb) * 4) = make_float4(o[0], o[1], o[2], o[3]);
                 }
                 fence();
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {          // 2 rows x 128 fp32 columns per instruction
-                    const int rr = tile_row0 + 2 * i + (lane >> 5);
+                for (int i = 0; i < 4; ++i) {          // 4 rows x 64 fp32 columns per instruction
+                    const int rl = 4 * i + (lane >> 4), rr = tile_row0 + rl, col = g * kOutCols + (lane & 15) * 4;
                     if (rr < rows_total) {
-                        const float4 w = *reinterpret_cast<const float4*>(out_lds + (2 * i + (lane >> 5)) * kOutPitch +
-                                                                          (lane & 31) * 16);
+                        const float4 w = *reinterpret_cast<const float4*>(out_lds + rl * kOutPitch + (lane & 15) * 16);
                         if (whole) {
                             uint2 o2;
                             o2.x = pack_bf16(w.x, w.y);
                             o2.y = pack_bf16(w.z, w.w);
-                            *reinterpret_cast<uint2*>(prm.out + ((long)b * rows_total + rr) * kDv + g * 128 + (lane & 31) * 4) = o2;
+                            *reinterpret_cast<uint2*>(prm.out + ((long)b * rows_total + rr) * kDv + col) = o2;
                         } else {
-                            *reinterpret_cast<float4*>(prm.part_o + (slot * rows_total + rr) * kDv + g * 128 + (lane & 31) * 4) = w;
+                            *reinterpret_cast<float4*>(prm.part_o + (slot * rows_total + rr) * kDv + col) = w;
                         }
                     }
                 }
@@ -438,7 +506,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 if (whole) {
                     if (prm.lse) prm.lse[(long)b * rows_total + row] = l > 0.0f ? (st[rt].m + __log2f(l)) * kLn2 : kNegInf;
                 } else {
-                    reinterpret_cast<float2*>(prm.part_ml)[slot * rows_total + row] = make_float2(st[rt].m, l);
+                    reinterpret_cast<float4*>(prm.part_ml)[slot * rows_total + row] = make_float4(st[rt].m, l, lq, 0.0f);
                 }
             }
         }
@@ -465,7 +533,7 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
         if (prm.lse && lane == 0) prm.lse[row] = kNegInf;
         return;
     }
-    const float2* ml = reinterpret_cast<const float2*>(prm.part_ml) + (long)fs.x * rows_total + th;
+    const float4* ml = reinterpret_cast<const float4*>(prm.part_ml) + (long)fs.x * rows_total + th;   // (m, l, lq, -)
     const float4* po = reinterpret_cast<const float4*>(prm.part_o + ((long)fs.x * rows_total + th) * kDv) + 2 * lane;
     const long po_stride = rows_total * (kDv / 4);
     float M = kNegInf;
@@ -474,10 +542,10 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
     const float m_use = (M == kNegInf) ? 0.0f : M;
-    float l = 0.0f;
+    float l = 0.0f, lq = 0.0f;
     float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     for (int s0 = 0; s0 < n; s0 += 4) {
-        float2 a[4];
+        float4 a[4];
         float4 o[4][2];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -490,13 +558,14 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
         for (int u = 0; u < 4; ++u) {
             const float w = s0 + u < n ? fast_exp2(a[u].x - m_use) : 0.0f;
             l = __builtin_fmaf(a[u].y, w, l);
+            lq = __builtin_fmaf(a[u].z, w, lq);
             acc[0] = __builtin_fmaf(o[u][0].x, w, acc[0]); acc[1] = __builtin_fmaf(o[u][0].y, w, acc[1]);
             acc[2] = __builtin_fmaf(o[u][0].z, w, acc[2]); acc[3] = __builtin_fmaf(o[u][0].w, w, acc[3]);
             acc[4] = __builtin_fmaf(o[u][1].x, w, acc[4]); acc[5] = __builtin_fmaf(o[u][1].y, w, acc[5]);
             acc[6] = __builtin_fmaf(o[u][1].z, w, acc[6]); acc[7] = __builtin_fmaf(o[u][1].w, w, acc[7]);
         }
     }
-    const float inv = l > 0.0f ? 1.0f / l : 0.0f;
+    const float inv = lq > 0.0f ? 1.0f / lq : 0.0f;
     uint4 w;
     w.x = pack_bf16(acc[0] * inv, acc[1] * inv);
     w.y = pack_bf16(acc[2] * inv, acc[3] * inv);
