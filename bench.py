@@ -163,6 +163,45 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline, use_graph=False):
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+def beam_search_bench():
+    """Host beam-search selection (section 4.5.1): the library's heap with early exit, the same entry
+    point sorting all candidates, and the numpy oracle, on the synthetic request batches; one thread."""
+    import numpy as np
+
+    import oracle
+    import paper_2510_14686_amd as xa
+    import workloads
+    res = {}
+    for name in sorted(workloads.BEAM_CONFIGS):
+        w = workloads.BEAM_CONFIGS[name]
+        beam, cand, tok = w.make()
+        want = oracle.beam_select(beam, cand, tok)
+        out = xa.xbeam_select(beam, cand, tok)
+        ok = all(np.array_equal(a, b) for a, b in zip(out[:3], want))
+
+        def timed(fn, min_s=0.3):
+            fn()
+            n, t0 = 0, time.perf_counter()
+            while time.perf_counter() - t0 < min_s:
+                fn()
+                n += 1
+            return (time.perf_counter() - t0) / n
+
+        t_heap = timed(lambda: xa.xbeam_select(beam, cand, tok, out_lp=out[0], out_parent=out[1], out_tok=out[2], visited=out[3]))
+        t_sort = timed(lambda: xa.xbeam_select(beam, cand, tok, flags=xa.XBEAM_FULL_SORT, out_lp=out[0], out_parent=out[1], out_tok=out[2], visited=out[3]))
+        out = xa.xbeam_select(beam, cand, tok)
+        t_orc = timed(lambda: oracle.beam_select(beam, cand, tok))
+        R, W, K = cand.shape
+        res[name] = {"n_req": R, "beam_width": W, "top_k": K, "matches_oracle": bool(ok),
+                     "us_per_request_heap_early_exit": 1e6 * t_heap / R, "us_per_request_full_sort": 1e6 * t_sort / R,
+                     "us_per_request_numpy_oracle": 1e6 * t_orc / R, "speedup_vs_full_sort": t_sort / t_heap,
+                     "candidates_examined_fraction": float(out[3].sum()) / (R * W * K)}
+        log("[%s] W=%d K=%d: heap+early exit %.1f us/request, full sort %.1f us/request (x%.1f), numpy oracle %.1f us/request, examined %.1f%% of the candidates, matches oracle: %s"
+            % (name, W, K, 1e6 * t_heap / R, 1e6 * t_sort / R, t_sort / t_heap, 1e6 * t_orc / R,
+               100 * res[name]["candidates_examined_fraction"], ok))
+    return res
+
+
 def run_mla_workload(w, steps, warmup, check_rows):
     """Latent-KV (MLA-shaped) decode: same protocol as run_workload; the roofline is the bf16 matrix peak."""
     import numpy as np
@@ -284,6 +323,7 @@ def main():
     ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
     ap.add_argument("--min-piece-tokens", type=int, default=0, help="override the minimum piece size (0 = default)")
     ap.add_argument("--path", type=int, default=0, help="inner loop: 0 automatic, 1 vector, 2 matrix cores")
+    ap.add_argument("--beam", action="store_true", help="host-only: time the beam-search selection step (heap with early exit vs sorting everything)")
     ap.add_argument("--mla-layout", type=int, default=0, help="latent-KV kernel: 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave")
     ap.add_argument("--pv-mode", type=int, default=0, help="matrix path p.V product: 0 default (bf16 MFMA, hi+lo parts), 1 fp32 MFMA, 2 single bf16 MFMA")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -298,6 +338,10 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); --gpus %d is not supported"
               % args.gpus, file=sys.stderr)
         sys.exit(2)
+
+    if args.beam:
+        print(json.dumps({"beam_search": beam_search_bench()}), flush=True)
+        return
 
     import torch
 

@@ -131,7 +131,8 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *                               MFMA on hi + lo bf16 parts of the weights (16 significant bits);
  *                               1 = fp32 MFMA (weights exact, slower); 2 = one bf16 MFMA (weights
  *                               rounded to bf16)
- *                               (xattn_mla_decode: 0 and 1 = hi + lo parts, 2 = one bf16 MFMA)
+ *                               (xattn_mla_decode: 0 and 2 = one bf16 MFMA, output normalised by the
+ *                               sum of the rounded weights; 1 = hi + lo parts, normalised by the exact sum)
  *   XATTN_CFG_MLA_LAYOUT        xattn_mla_decode workgroup shape for more than 64 query rows per sequence:
  *                               0 = automatic (8 waves of one 16-row tile), 1 = 4 waves of one tile,
  *                               2 = 4 waves of two tiles; for experiments, results do not depend on it

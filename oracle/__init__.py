@@ -16,6 +16,8 @@ from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
 
+from .beam import beam_select  # noqa: F401,E402  (numpy only)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "oracle_attn.c")
 _LIB_PATH = os.path.join(_HERE, "liboracle_attn.so")

@@ -7,4 +7,5 @@ from .binding import (XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_FREE, XTENSOR_PAGE_MA
                       xattn_mla_decode, xattn_write_kvcache, xtensor_close, xtensor_grow, xtensor_open, xtensor_page_info,
                       xtensor_pool_counts, xtensor_pool_create, xtensor_pool_destroy, xtensor_premap_async,
                       xtensor_premap_wait, xtensor_range_pages, xtensor_test_fake_counts, xtensor_test_fake_driver)
+from .binding import XBEAM_CHECK_INPUT, XBEAM_FULL_SORT, xbeam_select  # noqa: F401
 from .kvstore import KVStore  # noqa: F401

@@ -24,7 +24,8 @@ EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_s
            "xtensor_pool_create", "xtensor_pool_destroy", "xtensor_pool_counts", "xtensor_page_info",
            "xtensor_open", "xtensor_grow", "xtensor_premap_async", "xtensor_premap_wait", "xtensor_close",
            "xtensor_range_pages", "xtensor_test_fake_driver", "xtensor_test_fake_counts", "xattn_write_kvcache",
-           "xattn_mla_decode"]
+           "xattn_mla_decode", "xbeam_select"]
+XBEAM_FULL_SORT, XBEAM_CHECK_INPUT = 1, 2
 XTENSOR_PAGE_FREE, XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_MAPPED, XTENSOR_PAGE_REUSABLE = 0, 1, 2, 3
 
 
@@ -100,6 +101,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.xtensor_test_fake_counts.argtypes = [ctypes.POINTER(sz)] * 3
     lib.xattn_mla_decode.restype = i32
     lib.xattn_mla_decode.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    lib.xbeam_select.restype = i32
+    lib.xbeam_select.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
     lib.xattn_write_kvcache.restype = i32
     lib.xattn_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
     if path is None:
@@ -276,3 +279,30 @@ def xattn_mla_decode(q, c_ptrs, kv_lens, batch: int, q_len: int, n_heads: int, d
         stream = int(stream.cuda_stream)
     _check(load_library().xattn_mla_decode(_ptr(q), _ptr(c_ptrs), _ptr(kv_lens), batch, q_len, n_heads, d_latent,
                                            d_rope, ctypes.c_float(scale), _ptr(out), _ptr(lse), stream))
+
+
+def xbeam_select(beam_lp, cand_lp, cand_tok=None, flags: int = 0, out_lp=None, out_parent=None, out_tok=None,
+                 visited=None):
+    """Host beam-search selection on numpy arrays; see include/xbeam.h.  beam_lp float32 [R, W], cand_lp
+    float32 [R, W, K] descending along K, cand_tok int32 [R, W, K] or None.  Outputs are written into the
+    given arrays (allocated here when omitted) and returned as (out_lp, out_parent, out_tok, visited)."""
+    import numpy as np
+
+    def host(a, dtype, shape, name):
+        if not (isinstance(a, np.ndarray) and a.dtype == dtype and a.flags.c_contiguous and a.shape == shape):
+            raise TypeError("%s must be a C-contiguous %s array of shape %s" % (name, np.dtype(dtype).name, shape))
+        return a.ctypes.data
+
+    if not isinstance(cand_lp, np.ndarray) or cand_lp.ndim != 3:
+        raise TypeError("cand_lp must be a float32 array [n_req, beam_width, top_k]")
+    R, W, K = cand_lp.shape
+    out_lp = np.empty((R, W), np.float32) if out_lp is None else out_lp
+    out_parent = np.empty((R, W), np.int32) if out_parent is None else out_parent
+    out_tok = np.empty((R, W), np.int32) if out_tok is None else out_tok
+    visited = np.zeros(R, np.int64) if visited is None else visited
+    _check(load_library().xbeam_select(
+        host(beam_lp, np.float32, (R, W), "beam_lp"), host(cand_lp, np.float32, (R, W, K), "cand_lp"),
+        None if cand_tok is None else host(cand_tok, np.int32, (R, W, K), "cand_tok"), R, W, K, flags,
+        host(out_lp, np.float32, (R, W), "out_lp"), host(out_parent, np.int32, (R, W), "out_parent"),
+        host(out_tok, np.int32, (R, W), "out_tok"), host(visited, np.int64, (R,), "visited")))
+    return out_lp, out_parent, out_tok, visited

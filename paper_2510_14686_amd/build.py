@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libxattn.so")
-SOURCES = ["xattn_kernels.hip", "xattn_mla.hip", "xattn_api.cpp", "xtensor.cpp", "xtensor_pool.cpp"]
+SOURCES = ["xattn_kernels.hip", "xattn_mla.hip", "xattn_api.cpp", "xtensor.cpp", "xtensor_pool.cpp", "xbeam.cpp"]
 HEADERS = ["xattn_kernels.h", "xattn_device.h", "xattn_internal.h", "vmm_driver.h", os.path.join("..", "..", "include", "xattn.h")]
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                # packed-fp32 VALU forms are switched off for all device code of this library

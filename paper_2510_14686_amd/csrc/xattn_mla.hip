@@ -8,25 +8,29 @@
 // cached byte: the path is bound by the matrix cores and by the LDS that feeds them, not by HBM.
 //
 // Partition: the same token-stream pieces as the GQA kernel (section 4.4.3, "Layer 3").  A workgroup
-// owns one piece and up to 128 query rows (row = token * n_heads + head).  It has at most four waves,
-// one per SIMD, so that a wave may use the whole 512-entry register file: a wave owns one or two
-// tiles of 16 rows and keeps their Q (72 registers per tile) and their output accumulators (16 x 512
-// fp32 = 128 registers per tile) resident for the whole piece.  All waves share each 32-key block of
-// the cache through LDS:
+// owns one piece and up to 128 query rows (row = token * n_heads + head): eight waves, two per SIMD
+// (256 registers each), a wave owning one tile of 16 rows whose output accumulators (16 x 512 fp32 =
+// 128 registers) stay resident for the whole piece.  Of the tile's Q, 13 of the 18 MFMA steps stay in
+// registers (52); each lane parks its chunks of the other 5 in LDS and reads them back per block,
+// which leaves the registers for fetching operands ahead of the MFMAs.  (Workgroups of four waves,
+// one per SIMD with 512 registers and two tiles each, read every LDS operand half as often, but the
+// compiler keeps all MFMA results in the 256 accumulation registers and that layout needs 272.)
+// All waves share each 32-key block of the cache through LDS:
 //   * the block (32 x 1152 bytes, contiguous in memory) goes from HBM straight into LDS (buffer loads
 //     with the LDS destination, 1 KiB per wave instruction, no staging registers), once per
-//     workgroup, two LDS buffers, one barrier per block, the next block in flight during the
+//     workgroup; three LDS buffers, one barrier per block, two blocks in flight during the
 //     arithmetic.  In LDS the latent and the rope part of the rows sit in two areas with padded
 //     pitches chosen against bank conflicts (the LDS side of such a load is fixed to lane order, so
 //     the layout is made through the global address each lane fetches);
-//   * S^T = C Q^T: per 16-key tile 18 bf16 MFMA 16x16x32, the A operand (keys) read from LDS and used
-//     for both row tiles of the wave;
+//   * S^T = C Q^T: per 16-key tile 18 bf16 MFMA 16x16x32, the A operand (keys) read from LDS;
 //   * softmax on the accumulator layout: lane (kb, n) holds, of row n, the keys 4 kb + i of both key
 //     tiles, which is exactly the B operand (8 keys per lane) of the next product, so the weights
 //     never leave the lane; row maxima cross the four lane groups with lane-swap instructions;
 //   * O^T += C[:, 0:512]^T P^T: bf16 MFMA 16x16x32 over the 32 keys, the A operand (16 value columns x
-//     8 keys per lane) fetched with LDS transposing reads, again used for both row tiles; P goes in as
-//     hi + lo bf16 parts (two MFMAs) unless the caller asks for one rounded bf16.
+//     8 keys per lane) fetched with LDS transposing reads.  P goes in as one bf16 per weight and the
+//     output is normalised by the sum of those rounded weights; on request as hi + lo bf16 parts
+//     (two MFMAs, weights to 16 bits, normalised by the exact sum).
+// LDS reads are issued a few steps ahead of the MFMAs that use them, pinned with scheduling groups.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

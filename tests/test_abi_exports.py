@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol include/xattn.h declares (no GPU needed)."""
+"""The C-ABI library loads and exports every symbol include/*.h declares (no GPU needed)."""
 import ctypes
 import os
 import re
@@ -9,14 +9,17 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "xattn.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(x(?:attn|tensor)_[a-z_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names.update(re.findall(r"\b(x(?:attn|tensor|beam)_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_header_declares_the_boundary():
     names = _declared_functions()
-    for must in ("xattn_decode", "xtensor_map", "xtensor_unmap", "xattn_last_error"):
+    for must in ("xattn_decode", "xtensor_map", "xtensor_unmap", "xattn_last_error", "xbeam_select"):
         assert must in names
 
 

@@ -42,9 +42,13 @@ def _default_partition():
     import paper_2510_14686_amd as xa
     xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, 0)
     yield
     xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
     xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 0)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, 0)
+    xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, 0)
 
 
 @pytest.mark.parametrize("T,H", [(1, 128), (2, 128), (1, 16), (1, 32), (3, 64), (1, 8), (2, 24), (1, 144)])
@@ -86,6 +90,33 @@ def test_mla_xtensor_equals_plain_and_rows_past_kv_len_are_not_read():
     assert_parity(a_out, a_lse, ref_out, ref_lse, "mla padded")
 
 
+@pytest.mark.parametrize("pv_mode,layout", [(1, 0), (0, 1), (1, 1), (0, 2)])
+def test_mla_weight_precision_modes_and_workgroup_shapes(pv_mode, layout):
+    """hi + lo weights (PV mode 1) and the other workgroup shapes against the oracle; 144 heads: two row
+    groups, the second one partial."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    lens = [1, 3, 31, 32, 33, 100, 777, 2100]
+    q, cs = _case(230 + pv_mode, lens, 1, 144)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, pv_mode)
+    xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, layout)
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla pv_mode=%d layout=%d" % (pv_mode, layout))
+
+
+@pytest.mark.parametrize("scale_up", [4.0, 16.0])
+def test_mla_peaked_softmax(scale_up):
+    """Large scores: a few keys carry nearly all the weight, the case where rounding the weights to
+    bf16 shows most (the output is normalised by the sum of the rounded weights)."""
+    from gpu_util import assert_parity
+    lens = [2, 5, 40, 300, 1500]
+    q, cs = _case(240, lens, 2, 32)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE * scale_up)
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE * scale_up)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla peaked x%g" % scale_up)
+
+
 def test_mla_argument_checks():
     import paper_2510_14686_amd as xa
     for args in ((1, 1, 16, 512, 32), (1, 1, 16, 256, 64), (1, 17, 16, 512, 64), (1, 16, 512, 512, 64)):
@@ -95,6 +126,10 @@ def test_mla_argument_checks():
     with pytest.raises(xa.XattnError) as e:
         xa.xattn_mla_decode(0, 16, 16, 1, 1, 16, 512, 64, 0.1, 16)
     assert e.value.status == xa.binding.XATTN_EINVAL
+    for bad_scale in (0.0, -0.1, float("inf"), float("nan")):
+        with pytest.raises(xa.XattnError) as e:
+            xa.xattn_mla_decode(16, 16, 16, 1, 1, 16, 512, 64, bad_scale, 16)
+        assert e.value.status == xa.binding.XATTN_EINVAL
 
 
 @pytest.mark.parametrize("name", ["mla_decode", "mla_verify"])

@@ -231,6 +231,43 @@ class MlaWorkload:
         return replace(self, name=name, batch=batch, len_args=(max(1, lo // len_div), max(2, hi // len_div)),
                        n_heads=self.n_heads if n_heads is None else n_heads)
 
+@dataclass(frozen=True)
+class BeamWorkload:
+    """One beam-search selection step of a generative-recommendation request batch (host side): per
+    live sequence the top_k next-token log-probabilities of a softmax over `vocab` logits."""
+    name: str
+    n_req: int
+    beam_width: int
+    top_k: int
+    seed: int
+    vocab: int = 8192
+    logit_std: float = 2.5      # spread of the synthetic logits: the softmax is neither flat nor one-hot
+    note: str = ""
+
+    def make(self):
+        """(beam_lp [R, W] float32 descending, cand_lp [R, W, K] float32 descending along K, cand_tok int32).
+        The log-softmax and the top-k are the sampler's job, upstream of the selection: input preparation."""
+        R, W, K, V = self.n_req, self.beam_width, self.top_k, self.vocab
+        cand_lp = np.empty((R, W, K), np.float32)
+        cand_tok = np.empty((R, W, K), np.int32)
+        for r in range(R):
+            z = bf16_to_f32(normal_bf16(self.seed, 1 + r, W * V)).astype(np.float64).reshape(W, V) * self.logit_std
+            lse = np.log(np.sum(np.exp(z - z.max(axis=1, keepdims=True)), axis=1, keepdims=True)) + z.max(axis=1, keepdims=True)
+            lp = (z - lse).astype(np.float32)
+            idx = np.argsort(-lp, axis=1, kind="stable")[:, :K]
+            cand_tok[r] = idx.astype(np.int32)
+            cand_lp[r] = np.take_along_axis(lp, idx, axis=1)
+        u = uniform_u64(self.seed, 0, R * W).astype(np.float64) / float(1 << 64)
+        beam_lp = -np.sort(2.0 + 6.0 * u.reshape(R, W), axis=1).astype(np.float32)     # in [-8, -2], descending
+        return beam_lp, cand_lp, cand_tok
+
+
+BEAM_CONFIGS = {
+    "beam_small": BeamWorkload("beam_small", 2, 4, 8, seed=7, vocab=512, note="smallest beam width the paper plots"),
+    "beam_128": BeamWorkload("beam_128", 8, 128, 128, seed=8, note="largest beam width the paper plots, top_k = beam width"),
+    "beam_128x512": BeamWorkload("beam_128x512", 8, 128, 512, seed=9, note="large top_k: the host-bound regime"),
+}
+
 
 MLA_CONFIGS = {
     "mla_decode": MlaWorkload("mla_decode", 64, 1, 128, seed=5, len_args=(1024, 8192),
