@@ -333,7 +333,7 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     }
 }
 
-// grid.x = pieces, grid.y = groups of 16 * RT * NW rows; block = 64 * NW.  Wave w owns row tiles
+// grid.x = pieces (rounded up to a multiple of 8) x groups of 16 * RT * NW rows; block = 64 * NW.  Wave w owns row tiles
 // w * RT .. w * RT + RT - 1 of its group.
 template <int NW, int RT, bool kHiLo>
 __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
@@ -347,12 +347,18 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     const int T = prm.q_len, H = prm.n_heads, rows_total = T * H;
     const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, lane);
     const int per_xcd = (pl.n_pieces + 7) >> 3;
+    // Workgroup ids go round-robin over the 8 XCDs.  Of an XCD's workgroups, consecutive ones are the
+    // row groups of one piece: they run at the same time on the same XCD and share its L2, so the
+    // piece's cache rows come from HBM once.
     const int bid = blockIdx.x;
-    const int p = (bid & 7) * per_xcd + (bid >> 3);
+    const int n_groups = (rows_total + 16 * RT * NW - 1) / (16 * RT * NW);
+    const int slot_in_xcd = bid >> 3;
+    const int row_group = slot_in_xcd % n_groups;
+    const int p = (bid & 7) * per_xcd + slot_in_xcd / n_groups;
     const int s0 = piece_bound(pl, p), s1 = piece_bound(pl, p + 1);
-    const bool active = (bid >> 3) < per_xcd && p < pl.n_pieces && s0 < s1;
+    const bool active = slot_in_xcd / n_groups < per_xcd && p < pl.n_pieces && s0 < s1;
 
-    if (bid == 0 && blockIdx.y == 0 && tid < 64) {
+    if (bid == 0 && tid < 64) {
         // For the merge kernel: first partial slot and number of segments of every sequence.
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
@@ -391,7 +397,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     }
 
     // Row n of tile rt of this wave: row index within the sequence's T * H rows.
-    const int wave_row0 = blockIdx.y * (16 * RT * NW) + wave * (16 * RT);
+    const int wave_row0 = row_group * (16 * RT * NW) + wave * (16 * RT);
     char* q_lds = lds_q + wave * (RT * kQLdsWave) + lane * 16;
     char* out_lds = lds_q + wave * (RT * kQLdsWave);
     const DmaLane dma = dma_lane(lane);
@@ -602,7 +608,7 @@ hipError_t launch_mla_decode(const MlaParams& prm, hipStream_t stream, hipEvent_
     const int rows_total = prm.q_len * prm.n_heads;
     int nw = 1, rt = 1;
     mla_block_shape(rows_total, prm.layout, &nw, &rt);
-    dim3 grid((prm.n_pieces + 7) / 8 * 8, (rows_total + 16 * rt * nw - 1) / (16 * rt * nw));
+    dim3 grid((unsigned)((prm.n_pieces + 7) / 8 * 8 * ((rows_total + 16 * rt * nw - 1) / (16 * rt * nw))));
     hipError_t e;
     if (events && (e = hipEventRecord(events[0], stream)) != hipSuccess) return e;
     if (rt == 2) e = launch_mla_cfg<4, 2>(prm, grid, stream);
