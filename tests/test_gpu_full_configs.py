@@ -36,3 +36,29 @@ def test_full_size_workload(name, n_check):
     assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
     vmax = max(float(np.max(np.abs(bf16_to_f32(v)))) for v in vs)
     assert float(np.max(np.abs(got))) <= vmax * (1 + 2 ** -7)
+
+
+@pytest.mark.parametrize("name,n_check", [("mla_decode", 6), ("mla_verify", 4)])
+def test_full_size_latent_kv_workload(name, n_check):
+    """The two latent-KV workloads at full size, as bench.py launches them (automatic partition and
+    workgroup shape, xTensor ranges): sampled sequences element by element, every row bounded."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    from test_gpu_mla import gpu_mla
+    from workloads import MLA_CONFIGS
+    for key in (xa.XATTN_CFG_PIECES, xa.XATTN_CFG_MIN_PIECE_TOKENS, xa.XATTN_CFG_PV_MODE, xa.XATTN_CFG_MLA_LAYOUT):
+        xa.xattn_configure(key, 0)
+    w = MLA_CONFIGS[name]
+    lens = w.kv_lens()
+    q, cs = w.make_q(), w.make_cache(lens)
+    print("case", name, "tokens", int(lens.sum()), flush=True)
+    out_bits, lse = gpu_mla(q, cs, lens, w.scale, xtensor=w.xtensor, seed=w.seed)
+    B = w.batch
+    sel = sorted(set(np.linspace(0, B - 1, n_check).astype(int).tolist() + [int(np.argmax(lens)), int(np.argmin(lens))]))
+    ref_out, ref_lse = oracle.mla(q[sel], [cs[b] for b in sel], lens[sel], w.d_latent, w.scale)
+    print(name, "max_abs=%.2e rel_l2_rows=%.2e rel_l2=%.2e lse=%.2e"
+          % assert_parity(out_bits[sel], lse[sel], ref_out, ref_lse, name), flush=True)
+    got = bf16_to_f32(out_bits)
+    assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
+    vmax = max(float(np.max(np.abs(bf16_to_f32(c[:, :w.d_latent])))) for c in cs)
+    assert float(np.max(np.abs(got))) <= vmax * (1 + 2 ** -6)
