@@ -117,3 +117,47 @@ def test_capture_refuses_to_grow_the_workspace():
         graph.replay()
         torch.cuda.synchronize()
         assert float(marker[0]) == 1.0                             # the capture recorded the rest and replays
+
+
+def test_graph_replay_of_latent_kv_decode():
+    """xattn_mla_decode recorded once and replayed with other lengths and data: every replay against
+    the oracle and bit-identical to an eager call (eager work and synchronisations in between)."""
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    B, T, H, DQK, DV = 5, 2, 128, 576, 512
+    cap = 3000
+    scale = float(np.float32(1.0 / math.sqrt(192.0)))
+    cs = [normal_bf16(95, 1 + b, cap * DQK).reshape(cap, DQK) for b in range(B)]
+    with xa.KVStore(cs, cs, xtensor=True, seed=4) as store:
+        qd = torch.zeros((B, T, H, DQK), dtype=torch.int16, device="cuda")
+        lens_d = torch.full((B,), 100, dtype=torch.int32, device="cuda")
+        out = torch.zeros((B, T, H, DV), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((B, T, H), dtype=torch.float32, device="cuda")
+        out_e, lse_e = torch.zeros_like(out), torch.zeros_like(lse)
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):     # sizes the workspace: a capture cannot grow it
+            xa.xattn_mla_decode(qd, store.k_ptrs, lens_d, B, T, H, DV, DQK - DV, scale, out, lse, side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            xa.xattn_mla_decode(qd, store.k_ptrs, lens_d, B, T, H, DV, DQK - DV, scale, out, lse, side)
+        rng = np.random.RandomState(6)
+        for r in range(4):
+            lens = rng.randint(T, cap, size=B)
+            lens[r % B] = [T, 33, cap, 1025][r]
+            q = normal_bf16(96, r, B * T * H * DQK).reshape(B, T, H, DQK)
+            qd.copy_(torch.from_numpy(q.view(np.int16)))
+            lens_d.copy_(torch.from_numpy(lens.astype(np.int32)))
+            out.fill_(0x7FC0)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ref_out, ref_lse = oracle.mla(q, cs, lens, DV, scale)
+            got, got_lse = out.cpu().numpy().view(np.uint16), lse.cpu().numpy()
+            assert_parity(got, got_lse, ref_out, ref_lse, "latent-KV replay %d" % r)
+            xa.xattn_mla_decode(qd, store.k_ptrs, lens_d, B, T, H, DV, DQK - DV, scale, out_e, lse_e, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(out_e.cpu().numpy().view(np.uint16), got)
+            np.testing.assert_array_equal(lse_e.cpu().numpy(), got_lse)
