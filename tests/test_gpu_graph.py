@@ -99,18 +99,25 @@ def test_capture_refuses_to_grow_the_workspace():
             assert e.value.status == xa.binding.XATTN_ENOMEM
         finally:
             xa.xattn_set_workspace(None, 0)
-        # library-owned workspace, a shape larger than any call so far, under capture
-        xa.xattn_configure(xa.XATTN_CFG_PIECES, 65536)             # 64k pieces: a workspace larger than any earlier call left
+        # library-owned workspace, a shape larger than any call so far (64k pieces x 1024 query rows:
+        # tens of GB of partial results, far beyond what any other test leaves behind), under capture
+        T2, Hq2, Hkv2 = 16, 64, 16
+        ks2 = [normal_bf16(94, 10 + b, 64 * Hkv2 * D).reshape(64, Hkv2, D) for b in range(B)]
+        xa.xattn_configure(xa.XATTN_CFG_PIECES, 65536)
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         status = None
         try:
-            with torch.cuda.graph(graph, stream=side):
-                marker.add_(1.0)
-                try:
-                    xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, None, side)
-                except xa.XattnError as err:
-                    status = err.status
+            with xa.KVStore(ks2, ks2) as store2:
+                qd2 = torch.zeros((B, T2, Hq2, D), dtype=torch.int16, device="cuda")
+                out2 = torch.zeros((B, T2, Hq2, D), dtype=torch.int16, device="cuda")
+                torch.cuda.synchronize()
+                with torch.cuda.graph(graph, stream=side):
+                    marker.add_(1.0)
+                    try:
+                        xa.xattn_decode(qd2, store2.k_ptrs, store2.v_ptrs, lens_d, B, T2, Hq2, Hkv2, D, SCALE, out2, None, side)
+                    except xa.XattnError as err:
+                        status = err.status
         finally:
             xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
         assert status == xa.binding.XATTN_ENOMEM

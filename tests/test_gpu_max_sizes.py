@@ -1,0 +1,75 @@
+"""The largest arguments the two decode entry points accept, against the oracle: the maximum batch
+(4096 sequences, most of them a few keys long), the maximum number of query tokens (16) and of query
+rows per KV head (64), and for the latent-KV operator the maximum number of query rows per sequence
+(q_len * n_heads = 4096, 32 row groups per piece)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from workloads import bf16_to_f32, f32_to_bf16, normal_bf16, uniform_u64
+
+pytestmark = pytest.mark.gpu
+
+
+def _defaults():
+    import paper_2510_14686_amd as xa
+    for key in (xa.XATTN_CFG_PIECES, xa.XATTN_CFG_MIN_PIECE_TOKENS, xa.XATTN_CFG_PATH, xa.XATTN_CFG_PV_MODE,
+                xa.XATTN_CFG_MLA_LAYOUT):
+        xa.xattn_configure(key, 0)
+
+
+def test_maximum_batch():
+    from gpu_util import assert_parity, gpu_attn
+    _defaults()
+    B, T, Hq, Hkv, D = 4096, 1, 8, 2, 128
+    lens = (1 + (uniform_u64(70, 0, B) % np.uint64(40))).astype(np.int32)
+    lens[[5, 1000, 4095]] = [700, 1, 333]
+    q = normal_bf16(70, 1, B * T * Hq * D).reshape(B, T, Hq, D)
+    kv = normal_bf16(70, 2, int(lens.sum()) * Hkv * D * 2).reshape(-1, Hkv, D)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    ks = [kv[2 * off[b]:2 * off[b] + lens[b]] for b in range(B)]
+    vs = [kv[2 * off[b] + lens[b]:2 * off[b] + 2 * lens[b]] for b in range(B)]
+    scale = float(np.float32(1.0 / math.sqrt(D)))
+    out_bits, lse = gpu_attn(q, ks, vs, lens, scale)
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, scale)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "batch 4096")
+
+
+@pytest.mark.parametrize("T,Hq,Hkv", [(16, 8, 2), (16, 4, 4), (8, 16, 2)])
+def test_maximum_query_tokens_and_rows(T, Hq, Hkv):
+    from gpu_util import assert_parity, gpu_attn
+    _defaults()
+    D = 128
+    lens = np.array([T, T + 1, 100, 1000, 2500], np.int32)
+    B = len(lens)
+    q = normal_bf16(71, 0, B * T * Hq * D).reshape(B, T, Hq, D)
+    ks = [normal_bf16(71, 1 + 2 * b, int(L) * Hkv * D).reshape(int(L), Hkv, D) for b, L in enumerate(lens)]
+    vs = [normal_bf16(71, 2 + 2 * b, int(L) * Hkv * D).reshape(int(L), Hkv, D) for b, L in enumerate(lens)]
+    scale = float(np.float32(1.0 / math.sqrt(D)))
+    out_bits, lse = gpu_attn(q, ks, vs, lens, scale)
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, scale)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "T=%d Hq=%d Hkv=%d" % (T, Hq, Hkv))
+
+
+@pytest.mark.parametrize("B,T,H,lens", [(2, 16, 256, [16, 777]), (3, 1, 4096, [1, 40, 300]), (4096, 1, 16, None)])
+def test_latent_kv_maximum_rows_and_batch(B, T, H, lens):
+    from gpu_util import assert_parity
+    from test_gpu_mla import gpu_mla
+    _defaults()
+    DQK, DV = 576, 512
+    if lens is None:
+        lens = (1 + (uniform_u64(72, 0, B) % np.uint64(12))).astype(np.int32)
+        lens[[7, 4000]] = [500, 65]
+    lens = np.asarray(lens, np.int32)
+    q = f32_to_bf16(bf16_to_f32(normal_bf16(72, 1, B * T * H * DQK)) * np.float32(math.sqrt(192.0 / DQK))).reshape(B, T, H, DQK)
+    # halved (exact in bf16): with thousands of very short sequences some outputs would otherwise reach
+    # |x| >= 4, where rounding the output to bf16 alone moves it by up to 1.6e-2, past the 1e-2 bar
+    rows = f32_to_bf16(bf16_to_f32(normal_bf16(72, 2, int(lens.sum()) * DQK)) * np.float32(0.5)).reshape(-1, DQK)
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    cs = [rows[off[b]:off[b + 1]] for b in range(B)]
+    scale = float(np.float32(1.0 / math.sqrt(192.0)))
+    out_bits, lse = gpu_mla(q, cs, lens, scale)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, scale)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "latent-KV B=%d T=%d H=%d" % (B, T, H))
