@@ -31,11 +31,13 @@ HBM_PEAK_GBS = 8000.0
 # script (summaries under profiles/), scaled by the factor a plain copy kernel of known size gives.
 # None until measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/split_decode_kernel__<workload>.txt: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 of the decode kernel
-    "qwen3_8b_decode": 646598793,
-    "long_context": 1628775436,
-    "spec_verify": 2459933345,
-    "skewed_xtensor": 2154471091,
+    # profiles/<kernel>__<workload>.txt: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 of the decode kernel
+    "qwen3_8b_decode": 646595644,
+    "long_context": 1628775679,
+    "spec_verify": 2459946775,
+    "skewed_xtensor": 2154464867,
+    "mla_decode": 415676759,       # of which 88.5 MB are the partial results written
+    "mla_verify": 553627138,       # of which 176.9 MB written
 }
 
 
