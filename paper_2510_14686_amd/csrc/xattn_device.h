@@ -93,19 +93,28 @@ __device__ __forceinline__ void store_b128(void* base, uint32_t bytes, uint32_t 
 }
 
 // ---------------------------------------------------------------------------------- the plan
+// All keys of the batch form one stream that is cut into pieces of equal COST.  A sequence of L > 0
+// tokens occupies L + seg_cost positions of the stream: its tokens, then seg_cost positions that stand
+// for the fixed work every (piece, sequence) segment costs (first loads, Q, the stores of its result),
+// so a workgroup whose piece spans a sequence boundary gets correspondingly fewer tokens.  A piece
+// bound that falls into those extra positions means "the end of that sequence".  seg_cost = 0 gives
+// pieces of equal token count.
 struct Plan {
-    int total;      // N: tokens of the whole batch
+    int total;      // N: positions of the whole stream
     int n_pieces;   // pieces in use: min(launched pieces, N / minimum piece size), at least 1
+    int seg_cost;
 };
 
 __device__ __forceinline__ int clamp_len(int v) { return v > 0 ? v : 0; }
+// Stream positions of a sequence of `len` tokens (any sign).
+__device__ __forceinline__ int stream_len(int len, int seg_cost) { return len > 0 ? len + seg_cost : 0; }
 
 __device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ kv_lens, int batch, int n_pieces,
-                                          int min_piece, int lane) {
+                                          int min_piece, int seg_cost, int lane) {
     int total = 0;
     for (int base = 0; base < batch; base += 64) {
         const int i = base + lane;
-        total += wave_sum_i(i < batch ? clamp_len(kv_lens[i]) : 0);
+        total += wave_sum_i(i < batch ? stream_len(kv_lens[i], seg_cost) : 0);
     }
     total = __builtin_amdgcn_readfirstlane(total);
     int n = total / min_piece;
@@ -113,18 +122,19 @@ __device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ kv_lens, i
     Plan pl;
     pl.total = total;
     pl.n_pieces = n < n_pieces ? n : n_pieces;
+    pl.seg_cost = seg_cost;
     return pl;
 }
 
-// Piece p owns stream tokens [piece_bound(p), piece_bound(p + 1)): p * N / n_pieces rounded to a
-// multiple of the 16-key block, so every piece is within 16 tokens of N / n_pieces and all are used.
+// Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): p * N / n_pieces rounded to a
+// multiple of the 16-key block, so every piece is within 16 positions of N / n_pieces and all are used.
 __device__ __forceinline__ int piece_bound(const Plan& pl, int p) {
     if (p >= pl.n_pieces) return pl.total;
     const long x = (long)p * pl.total / pl.n_pieces;
     const int r = (int)((x + kBlockKeys / 2) / kBlockKeys) * kBlockKeys;
     return r < pl.total ? r : pl.total;
 }
-// The piece that owns stream token x (0 <= x < N).
+// The piece that owns stream position x (0 <= x < N).
 __device__ __forceinline__ int piece_of(const Plan& pl, int x) {
     int p = (int)((long)x * pl.n_pieces / pl.total);
     while (p + 1 < pl.n_pieces && piece_bound(pl, p + 1) <= x) ++p;

@@ -505,6 +505,10 @@ __device__ __forceinline__ void matrix_finish(const MatrixState& st, const Matri
 // ---------------------------------------------------------------------------------- decode kernel
 // grid.x = pieces, grid.y = row tiles of R rows, grid.z = groups of up to 8 KV heads; block = 64 * heads.
 // kMatrix selects the matrix path (R must be 16 then).
+// Fixed work of a (piece, sequence) segment in token units for the partition (0 = pieces of equal token
+// count; 16 measured best of 0 / 16 / 48: 0.2 to 1 % on the four large workloads).
+constexpr int kGqaSegCost = 16;
+
 template <int R, bool kMatrix, int kPv>
 __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     __shared__ __attribute__((aligned(16))) char lds[kMatrix ? kMaxWavesPerBlock * kLdsPerWave : 16];
@@ -512,7 +516,7 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     const int wave = threadIdx.x >> 6;
     const int kvh = blockIdx.z * kMaxWavesPerBlock + wave;
     if (kvh >= prm.n_kv_heads) return;
-    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, lane);
+    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kGqaSegCost, lane);
 
     // Piece index: consecutive workgroups go to different XCDs, so give each XCD one contiguous
     // eighth of the token stream.
@@ -527,11 +531,13 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
             const int i = base + lane;
-            const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int len = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int v = stream_len(len, pl.seg_cost);
             const int incl = wave_incl_scan_i(v, lane) + run;
             if (i < prm.batch) {
-                const int first = v > 0 ? piece_of(pl, incl - v) : 0;
-                const int n_seg = v > 0 ? piece_of(pl, incl - 1) - first + 1 : 0;
+                // the pieces from the one with the sequence's first token to the one with its last
+                const int first = len > 0 ? piece_of(pl, incl - v) : 0;
+                const int n_seg = len > 0 ? piece_of(pl, incl - v + len - 1) - first + 1 : 0;
                 reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
             }
             run = __shfl(incl, 63, 64);
@@ -540,13 +546,13 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     if (!active) return;
 
 
-    // Locate the sequence that holds stream token s0.
+    // Locate the sequence that holds stream position s0; j = offset within its L + seg_cost positions.
     int b = 0, j = 0;
     {
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
             const int i = base + lane;
-            const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int v = i < prm.batch ? stream_len(prm.kv_lens[i], pl.seg_cost) : 0;
             const int incl = wave_incl_scan_i(v, lane) + run;
             const unsigned long long hit = __ballot(s0 >= incl - v && s0 < incl);
             if (hit) {
@@ -566,23 +572,27 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     seg.kvh = kvh;
     seg.row0 = blockIdx.y * R;
     seg.n_rows = rows_total - seg.row0 < R ? rows_total - seg.row0 : R;
-    int remaining = s1 - s0;
+    int remaining = s1 - s0;            // stream positions left in this piece
     // Next (piece, sequence) intersection of this piece, in stream order; false when the piece is done.
     auto next_segment = [&](Segment& out) {
         while (remaining > 0 && b < prm.batch) {
             const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
             if (L == 0) { ++b; continue; }
-            const int n = (L - j < remaining) ? L - j : remaining;
-            out = seg;
-            out.b = b;
-            out.L = L;
-            out.j0 = j;
-            out.j1 = j + n;
-            out.slot = p + b;
-            out.whole = (n == L);
-            remaining -= n;
+            // the piece's share of this sequence's L + seg_cost positions, and the tokens among them
+            const int n_pos = (L + pl.seg_cost - j < remaining) ? L + pl.seg_cost - j : remaining;
+            const int j0 = j < L ? j : L, j1 = j + n_pos < L ? j + n_pos : L;
+            remaining -= n_pos;
+            const int bb = b;
             ++b;
             j = 0;
+            if (j1 <= j0) continue;                    // only the sequence's extra positions: no tokens
+            out = seg;
+            out.b = bb;
+            out.L = L;
+            out.j0 = j0;
+            out.j1 = j1;
+            out.slot = p + bb;
+            out.whole = (j0 == 0 && j1 == L);
             return true;
         }
         return false;

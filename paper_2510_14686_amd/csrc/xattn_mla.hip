@@ -67,6 +67,9 @@ constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
 constexpr int kOutCols = 64;                     // epilogue: 16 rows x 64 fp32 columns at a time, padded
 constexpr int kOutPitch = kOutCols * 4 + 16;
 constexpr int kLdsOutPerWave = 16 * kOutPitch;
+// A segment's fixed work (first block's latency, Q, output staging and stores: about 11 us measured)
+// in units of one token's share of the block loop (2.55 us per 32 tokens).
+constexpr int kMlaSegCost = 128;
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 4, n = lane & 15;
     const int T = prm.q_len, H = prm.n_heads, rows_total = T * H;
-    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, lane);
+    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kMlaSegCost, lane);
     const int per_xcd = (pl.n_pieces + 7) >> 3;
     // Workgroup ids go round-robin over the 8 XCDs.  Of an XCD's workgroups, consecutive ones are the
     // row groups of one piece: they run at the same time on the same XCD and share its L2, so the
@@ -363,11 +366,13 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
             const int i = base + lane;
-            const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int len = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int v = stream_len(len, pl.seg_cost);
             const int incl = wave_incl_scan_i(v, lane) + run;
             if (i < prm.batch) {
-                const int first = v > 0 ? piece_of(pl, incl - v) : 0;
-                const int n_seg = v > 0 ? piece_of(pl, incl - 1) - first + 1 : 0;
+                // the pieces from the one with the sequence's first token to the one with its last
+                const int first = len > 0 ? piece_of(pl, incl - v) : 0;
+                const int n_seg = len > 0 ? piece_of(pl, incl - v + len - 1) - first + 1 : 0;
                 reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
             }
             run = __shfl(incl, 63, 64);
@@ -375,13 +380,13 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     }
     if (!active) return;       // the whole workgroup: every wave computed the same plan
 
-    // Locate the sequence that holds stream token s0.
+    // Locate the sequence that holds stream position s0; j = offset within its L + seg_cost positions.
     int b = 0, j = 0;
     {
         int run = 0;
         for (int base = 0; base < prm.batch; base += 64) {
             const int i = base + lane;
-            const int v = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
+            const int v = i < prm.batch ? stream_len(prm.kv_lens[i], pl.seg_cost) : 0;
             const int incl = wave_incl_scan_i(v, lane) + run;
             const unsigned long long hit = __ballot(s0 >= incl - v && s0 < incl);
             if (hit) {
@@ -411,13 +416,16 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    int remaining = s1 - s0;
+    int remaining = s1 - s0;            // stream positions left in this piece
     while (remaining > 0 && b < prm.batch) {
         const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
         if (L == 0) { ++b; continue; }
-        const int n_tok = (L - j < remaining) ? L - j : remaining;
-        const int j0 = j, j1 = j + n_tok;
-        const bool whole = (n_tok == L);
+        // the piece's share of this sequence's L + seg_cost positions, and the tokens among them
+        const int n_pos = (L + pl.seg_cost - j < remaining) ? L + pl.seg_cost - j : remaining;
+        const int j0 = j < L ? j : L, j1 = j + n_pos < L ? j + n_pos : L;
+        remaining -= n_pos;
+        if (j1 <= j0) { ++b; j = 0; continue; }       // only the sequence's extra positions: no tokens
+        const bool whole = (j0 == 0 && j1 == L);
         const long slot = (long)p + b;
         const unsigned long long cbytes = (unsigned long long)L * kRowB;
         const uint64_t caddr = (uint64_t)(uintptr_t)prm.c_ptrs[b];
@@ -520,7 +528,6 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 }
             }
         }
-        remaining -= n_tok;
         ++b;
         j = 0;
     }

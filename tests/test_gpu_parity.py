@@ -146,7 +146,9 @@ def test_causal_block_equals_sequential_calls_on_gpu():
         out1, lse1 = gpu_attn(np.ascontiguousarray(q[:, t:t + 1]), ks, vs, lens_t, SCALE)
         a = wl.bf16_to_f32(out4[:, t]).astype(np.float64)
         b = wl.bf16_to_f32(out1[:, 0]).astype(np.float64)
-        assert np.max(np.abs(a - b)) <= 2e-2 * max(1.0, np.max(np.abs(b))) * 2 ** -6   # a bf16 ulp or two
+        # the two calls split the keys differently, so fp32 sums differ in the last bits and a bf16
+        # output may round the other way: at most one bf16 ulp (2^-7 relative), element by element
+        assert np.all(np.abs(a - b) <= 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 1e-30)
         assert np.max(np.abs(lse4[:, t] - lse1[:, 0])) < 1e-4
 
 
