@@ -318,8 +318,8 @@ def xtensor_page_ops(n_pages=256, reps=5):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="qwen3_8b_decode")
     ap.add_argument("--only", action="store_true", help="measure only --workload, not the other large workloads")
     ap.add_argument("--pieces", type=int, default=0, help="override the number of pieces of the partition (0 = automatic)")
