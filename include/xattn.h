@@ -60,7 +60,9 @@ const char* xattn_last_error(void);
  * v_ptrs   DEVICE  same layout as K
  * kv_lens  DEVICE  int32[batch]; keys visible to the LAST new token, i.e. prefix + q_len (the new
  *                  tokens' K/V are already written).  Read on the device only.  A value < q_len
- *                  leaves the tokens without visible keys with out = 0 and lse = -inf.
+ *                  leaves the tokens without visible keys with out = 0 and lse = -inf.  The device
+ *                  adds the lengths up in 32 bits: the sum over the batch of (kv_lens[b] + 128) must
+ *                  stay below 2^31 (the host cannot check it; results are undefined beyond).
  * batch    1..4096;  q_len 1..16;  head_dim must be 128;  n_q_heads a multiple of n_kv_heads;
  *          (n_q_heads / n_kv_heads) * q_len <= 64.  Otherwise XATTN_EUNSUPPORTED.
  * scale    multiplies the scores before the softmax (the caller's fp32 value, e.g. 1/sqrt(128))
