@@ -59,7 +59,7 @@ constexpr int kTileB = 16 * kPitch;              // from key tile 0 to key tile 
 constexpr int kTailTileB = 16 * kTailPitch;
 constexpr int kMainSteps = 1024 / 64;            // MFMA steps 0..15 read the latent part, 16..17 the tail
 constexpr int kQSteps = kDqk / 32;               // 18 MFMA steps of 32 columns
-constexpr int kQRegSteps = 13;                   // Q columns 0 .. 32 * 9 - 1 stay in registers, the rest of Q in LDS
+constexpr int kQRegSteps = 13;                   // Q columns 0 .. 32 * 13 - 1 stay in registers, the rest of Q in LDS
 constexpr int kQLdsWave = (kQSteps - kQRegSteps) * 1024;   // per 16-row tile: one 16-byte chunk per lane and step
 constexpr int kQAhead = 2;                       // key fragments in flight ahead of the MFMAs, in steps
 constexpr int kVAhead = 1;                       // value fragments in flight ahead of the MFMAs, in tile pairs
