@@ -32,12 +32,12 @@ HBM_PEAK_GBS = 8000.0
 # None until measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/<kernel>__<workload>.txt: FETCH_SIZE x 2.0000 + WRITE_SIZE x 1.0000 of the decode kernel
-    "qwen3_8b_decode": 646595644,
-    "long_context": 1628775679,
-    "spec_verify": 2459946775,
-    "skewed_xtensor": 2154464867,
-    "mla_decode": 415676759,       # of which 88.5 MB are the partial results written
-    "mla_verify": 553627138,       # of which 176.9 MB written
+    "qwen3_8b_decode": 646547269,
+    "long_context": 1628809212,
+    "spec_verify": 2459629508,
+    "skewed_xtensor": 2154417468,
+    "mla_decode": 413566618,       # of which 86.9 MB are the partial results written
+    "mla_verify": 543842570,       # of which 171.7 MB written
 }
 
 
