@@ -267,7 +267,14 @@ def run_mla_workload(w, steps, warmup, check_rows):
         lse_h = lse.cpu().numpy()
         sel = list(range(B)) if check_rows is None or check_rows >= B else \
             sorted(set(np.linspace(0, B - 1, check_rows).astype(int).tolist() + [int(np.argmax(lens)), int(np.argmin(lens))]))
+        t0 = time.time()
         ref_out, ref_lse = oracle.mla(q[sel], [cs[b] for b in sel], lens[sel], w.d_latent, w.scale)
+        t_cpu = time.time() - t0
+        sel_tokens = int(lens[sel].sum())
+        sel_flops = sel_tokens * T * H * 2 * (w.d_qk + w.d_latent)
+        res["cpu_baseline"] = {"value": sel_flops / t_cpu / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                               "kind": "oracle", "sample": "%d of %d sequences (%d cached tokens), one pass, %.2f s"
+                                                           % (len(sel), B, sel_tokens, t_cpu)}
         max_abs, rel_rows, rel_all, lse_err = errors(out_h[sel], lse_h[sel], ref_out, ref_lse)
         res["parity"] = {"sequences_checked": len(sel), "max_abs": max_abs, "max_row_rel_l2": rel_rows,
                          "rel_l2": rel_all, "lse_max_abs": lse_err,
@@ -382,7 +389,7 @@ def main():
                           "config": {k: r[k] for k in ("workload", "batch", "q_len", "n_heads", "d_latent", "d_rope",
                                                        "kv_tokens", "kv_bytes", "flops")},
                           "kv_read_GBps": r["kv_read_GBps"], "token_steps_per_s": r["token_steps_per_s"],
-                          "roofline": r["roofline"], "parity": r["parity"]}), flush=True)
+                          "roofline": r["roofline"], "cpu_baseline": r["cpu_baseline"], "parity": r["parity"]}), flush=True)
         return
     head = workloads.CONFIGS[args.workload]
     main_res = run_workload(head, args.steps, args.warmup, args.check_sequences, cpu_baseline=True, use_graph=args.graph)
