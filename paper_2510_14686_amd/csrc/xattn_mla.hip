@@ -70,6 +70,7 @@ constexpr int kLdsOutPerWave = 16 * kOutPitch;
 // A segment's fixed work (first block's latency, Q, output staging and stores: about 11 us measured)
 // in units of one token's share of the block loop (2.55 us per 32 tokens).
 constexpr int kMlaSegCost = 128;
+constexpr float kLazyLog2 = 8.0f;                // slack of the softmax reference maximum, in powers of two
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
@@ -275,7 +276,11 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
         }
         float mx = fmaxf(fmaxf(fmaxf(p[0], p[1]), fmaxf(p[2], p[3])), fmaxf(fmaxf(p[4], p[5]), fmaxf(p[6], p[7])));
         mx = kb_max(mx) * scale_log2;
-        const float m_new = fmaxf(st[rt].m, mx);
+        // The reference maximum follows the row's maximum lazily: it moves only when a block exceeds
+        // it by more than kLazyLog2, so weights reach 2^kLazyLog2 at most (harmless in fp32 sums and in
+        // bf16's relative precision) and the rescaling of the 128 accumulators below, which would
+        // otherwise run in most blocks (some row of the tile sees a new maximum), runs about once.
+        const float m_new = mx > st[rt].m + kLazyLog2 ? mx : st[rt].m;
         const float m_use = (m_new == kNegInf) ? 0.0f : m_new;
         const float alpha = fast_exp2(st[rt].m - m_use);
         float sum = 0.0f;
