@@ -305,12 +305,12 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     int st = device_state(&d, nullptr);
     if (st != XATTN_OK) return st;
     const int n_pieces = pieces_for(d->n_cu);
-    // per-sequence table, partial (m, l, lq) per row, partial rows of 512 fp32
+    // per-sequence table, partial (m, l, lq, 1 / scale) per row, partial rows of 512 fp16
     const size_t slots = (size_t)n_pieces + (size_t)batch;
     const size_t rows = (size_t)q_len * (size_t)n_heads;
     const size_t ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
-    const size_t o_off = ml_off + align_up(slots * rows * 4 * sizeof(float), 256);      // (m, l, lq, -) per partial row
-    const size_t total = o_off + align_up(slots * rows * 512 * sizeof(float), 256);
+    const size_t o_off = ml_off + align_up(slots * rows * 4 * sizeof(float), 256);      // (m, l, lq, 1 / scale) per partial row
+    const size_t total = o_off + align_up(slots * rows * 512 * sizeof(uint16_t), 256);
     char* ws = nullptr;
     st = acquire_workspace(d, total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);
     if (st != XATTN_OK) return st;
@@ -327,7 +327,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.lse = lse;
     prm.meta = reinterpret_cast<int32_t*>(ws);
     prm.part_ml = reinterpret_cast<float*>(ws + ml_off);
-    prm.part_o = reinterpret_cast<float*>(ws + o_off);
+    prm.part_o = reinterpret_cast<uint16_t*>(ws + o_off);
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;

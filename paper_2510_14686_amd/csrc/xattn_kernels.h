@@ -59,8 +59,8 @@ struct MlaParams {
     float scale_log2;
     uint16_t* out;                   // bf16 [batch, q_len, n_heads, 512]
     float* lse;                      // fp32 [batch, q_len, n_heads] or null
-    float* part_o;                   // fp32 [slots, q_len * n_heads, 512]
-    float* part_ml;                  // fp32 [slots, q_len * n_heads, 2]
+    uint16_t* part_o;                // fp16 [slots, q_len * n_heads, 512]: partial rows, each times its own scale
+    float* part_ml;                  // fp32 [slots, q_len * n_heads, 4]: (max, sum, sum of rounded weights, 1 / scale)
     int32_t* meta;                   // int32 [batch, 2]
     int n_pieces, min_piece_tokens;
     int layout;                      // 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave

@@ -67,9 +67,10 @@ constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
 constexpr int kOutCols = 64;                     // epilogue: 16 rows x 64 fp32 columns at a time, padded
 constexpr int kOutPitch = kOutCols * 4 + 16;
 constexpr int kLdsOutPerWave = 16 * kOutPitch;
-// A segment's fixed work (first block's latency, Q, output staging and stores: about 11 us measured)
-// in units of one token's share of the block loop (2.55 us per 32 tokens).
-constexpr int kMlaSegCost = 128;
+// A segment's fixed work (first block's latency, Q, output staging and stores; measured: workgroups
+// with two segments finish 13 us later than their token count says) in units of one token's share of
+// the block loop (2.3 us per 32 tokens).
+constexpr int kMlaSegCost = 192;
 constexpr float kLazyLog2 = 8.0f;                // slack of the softmax reference maximum, in powers of two
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
@@ -172,6 +173,13 @@ __device__ __forceinline__ float kb_sum(float x) {
     x = a + b;
     swap32(x, a, b);
     return a + b;
+}
+
+// Two values rounded to fp16 (nearest even) and packed.
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_f16(float a, float b) {
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
 }
 
 // Scheduling groups (the group sizes must be compile-time constants, hence the templates).
@@ -497,7 +505,24 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         for (int rt = 0; rt < RT; ++rt) {
             const float l = kb_sum(st[rt].l);
             const float lq = kHiLo ? l : kb_sum(st[rt].lq);
-            const float sc = whole ? (lq > 0.0f ? 1.0f / lq : 0.0f) : 1.0f;
+            // A partial row goes out as fp16 after scaling its largest magnitude to 2^15 (the scale's
+            // inverse is kept in fp32 beside the row's m and l): half the bytes of fp32 to write here
+            // and to read back in the merge.  Every element keeps 11 significant bits of its own
+            // (down to 2^-29 of the row's maximum), so a few large columns cost the others nothing.
+            // The scale is capped so that rows of denormal size do not overflow it.
+            float sc, inv_scale = 0.0f;
+            if (whole) {
+                sc = lq > 0.0f ? 1.0f / lq : 0.0f;
+            } else {
+                float amax = 0.0f;
+#pragma unroll
+                for (int ct = 0; ct < kColTiles; ++ct)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) amax = fmaxf(amax, __builtin_fabsf(st[rt].o[ct][i]));
+                amax = kb_max(amax);
+                sc = amax > 0.0f ? fminf(32768.0f / amax, 0x1.0p100f) : 0.0f;
+                inv_scale = amax > 0.0f ? 1.0f / sc : 0.0f;
+            }
             const int tile_row0 = wave_row0 + 16 * rt;
 #pragma unroll
             for (int g = 0; g < kDv / kOutCols; ++g) {
@@ -512,13 +537,15 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                     const int rl = 4 * i + (lane >> 4), rr = tile_row0 + rl, col = g * kOutCols + (lane & 15) * 4;
                     if (rr < rows_total) {
                         const float4 w = *reinterpret_cast<const float4*>(out_lds + rl * kOutPitch + (lane & 15) * 16);
+                        uint2 o2;
                         if (whole) {
-                            uint2 o2;
                             o2.x = pack_bf16(w.x, w.y);
                             o2.y = pack_bf16(w.z, w.w);
                             *reinterpret_cast<uint2*>(prm.out + ((long)b * rows_total + rr) * kDv + col) = o2;
                         } else {
-                            *reinterpret_cast<float4*>(prm.part_o + (slot * rows_total + rr) * kDv + col) = w;
+                            o2.x = pack_f16(w.x, w.y);
+                            o2.y = pack_f16(w.z, w.w);
+                            *reinterpret_cast<uint2*>(prm.part_o + (slot * rows_total + rr) * kDv + col) = o2;
                         }
                     }
                 }
@@ -529,7 +556,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 if (whole) {
                     if (prm.lse) prm.lse[(long)b * rows_total + row] = l > 0.0f ? (st[rt].m + __log2f(l)) * kLn2 : kNegInf;
                 } else {
-                    reinterpret_cast<float4*>(prm.part_ml)[slot * rows_total + row] = make_float4(st[rt].m, l, lq, 0.0f);
+                    reinterpret_cast<float4*>(prm.part_ml)[slot * rows_total + row] = make_float4(st[rt].m, l, lq, inv_scale);
                 }
             }
         }
@@ -538,7 +565,8 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     }
 }
 
-// One wave per output row of 512 columns; lane holds columns 8*lane .. 8*lane+7.
+// One wave per output row of 512 columns; lane holds columns 8*lane .. 8*lane+7.  A partial row is 512
+// fp16 values times its own scale (the fourth value of its (m, l, lq, 1 / scale) record).
 __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
     const int lane = threadIdx.x & 63;
     const long rows_total = (long)prm.q_len * prm.n_heads;
@@ -555,9 +583,9 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
         if (prm.lse && lane == 0) prm.lse[row] = kNegInf;
         return;
     }
-    const float4* ml = reinterpret_cast<const float4*>(prm.part_ml) + (long)fs.x * rows_total + th;   // (m, l, lq, -)
-    const float4* po = reinterpret_cast<const float4*>(prm.part_o + ((long)fs.x * rows_total + th) * kDv) + 2 * lane;
-    const long po_stride = rows_total * (kDv / 4);
+    const float4* ml = reinterpret_cast<const float4*>(prm.part_ml) + (long)fs.x * rows_total + th;   // (m, l, lq, 1 / scale)
+    const uint4* po = reinterpret_cast<const uint4*>(prm.part_o + ((long)fs.x * rows_total + th) * kDv) + lane;
+    const long po_stride = rows_total * (kDv / 8);
     float M = kNegInf;
     for (int base = 0; base < n; base += 64)
         if (base + lane < n) M = fmaxf(M, ml[(base + lane) * rows_total].x);
@@ -568,23 +596,26 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
     float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     for (int s0 = 0; s0 < n; s0 += 4) {
         float4 a[4];
-        float4 o[4][2];
+        uint4 o[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < n ? s0 + u : n - 1;
             a[u] = ml[s * rows_total];
-            o[u][0] = po[s * po_stride];
-            o[u][1] = po[s * po_stride + 1];
+            o[u] = po[s * po_stride];
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const float w = s0 + u < n ? fast_exp2(a[u].x - m_use) : 0.0f;
             l = __builtin_fmaf(a[u].y, w, l);
             lq = __builtin_fmaf(a[u].z, w, lq);
-            acc[0] = __builtin_fmaf(o[u][0].x, w, acc[0]); acc[1] = __builtin_fmaf(o[u][0].y, w, acc[1]);
-            acc[2] = __builtin_fmaf(o[u][0].z, w, acc[2]); acc[3] = __builtin_fmaf(o[u][0].w, w, acc[3]);
-            acc[4] = __builtin_fmaf(o[u][1].x, w, acc[4]); acc[5] = __builtin_fmaf(o[u][1].y, w, acc[5]);
-            acc[6] = __builtin_fmaf(o[u][1].z, w, acc[6]); acc[7] = __builtin_fmaf(o[u][1].w, w, acc[7]);
+            const float ws = w * a[u].w;             // weight times the inverse of the row's scale
+            const uint32_t q[4] = {o[u].x, o[u].y, o[u].z, o[u].w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const f32x2_t v = __builtin_convertvector(__builtin_bit_cast(f16x2_t, q[c]), f32x2_t);
+                acc[2 * c] = __builtin_fmaf(v[0], ws, acc[2 * c]);
+                acc[2 * c + 1] = __builtin_fmaf(v[1], ws, acc[2 * c + 1]);
+            }
         }
     }
     const float inv = lq > 0.0f ? 1.0f / lq : 0.0f;

@@ -117,6 +117,31 @@ def test_mla_peaked_softmax(scale_up):
     assert_parity(out_bits, lse, ref_out, ref_lse, "mla peaked x%g" % scale_up)
 
 
+def test_mla_outlier_value_columns_cost_the_other_columns_nothing():
+    """One latent column in eight 512 times larger than the rest (Q's same columns 512 times smaller, so the
+    scores do not change): split sequences pass their partial rows in a 16-bit form, and every column,
+    large or small, must still meet the bar at its own magnitude."""
+    from gpu_util import assert_parity
+    lens = [700, 3000, 9000]                       # split over many workgroups
+    big = np.arange(5, DV, 8)                      # 64 of the 512 value columns
+    q, cs = _case(245, lens, 1, 128)
+    qf = bf16_to_f32(q).copy()
+    qf[..., big] /= np.float32(512.0)               # powers of two: exact in bf16
+    q2 = f32_to_bf16(qf).reshape(q.shape)
+    cs2 = []
+    for c in cs:
+        cf = bf16_to_f32(c).copy()
+        cf[:, big] *= np.float32(512.0)
+        cs2.append(f32_to_bf16(cf).reshape(c.shape))
+    ref_out, ref_lse = oracle.mla(q2, cs2, lens, DV, SCALE)
+    out_bits, lse = gpu_mla(q2, cs2, lens, SCALE)
+    small = np.setdiff1d(np.arange(DV), big)
+    got = bf16_to_f32(out_bits).reshape(ref_out.shape)
+    assert_parity(f32_to_bf16(got[..., small]), lse, ref_out[..., small], ref_lse, "mla outliers, ordinary columns")
+    assert_parity(f32_to_bf16(got[..., big] / np.float32(512.0)), None, ref_out[..., big] / 512.0, ref_lse,
+                  "mla outliers, large columns")
+
+
 def test_mla_argument_checks():
     import paper_2510_14686_amd as xa
     for args in ((1, 1, 16, 512, 32), (1, 1, 16, 256, 64), (1, 17, 16, 512, 64), (1, 16, 512, 512, 64)):
