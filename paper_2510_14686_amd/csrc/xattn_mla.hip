@@ -447,7 +447,6 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                             (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(caddr >> 32) & 0xffffu)),
                             cbytes > 0xffffffffull ? 0xffffffffu : (uint32_t)cbytes, 0x00020000u};
 
-        block_to_lds<NW>(lds_c, rc, j0, wave, dma);        // block 0 -> buffer 0
         // Q operand: lane (kb, n) holds columns 32 step + 8 kb .. + 7 of row n of each tile.
         bf16x8_t qop[RT][kQRegSteps];
         int lim[RT];
@@ -473,6 +472,9 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
             st[rt].lq = 0.0f;
         }
 
+        // Block 0 -> buffer 0, behind the Q loads: those do not need the sequence's base address, whose
+        // own load they now cover.
+        block_to_lds<NW>(lds_c, rc, j0, wave, dma);
         // Q is used here, before the loop, so that the wait for its loads sits here as well: a wait
         // inside the loop would also wait for the block loads that were just issued.
 #pragma unroll
