@@ -36,8 +36,8 @@ MEASURED_TRAFFIC_BYTES = {
     "long_context": 1628809212,
     "spec_verify": 2459629508,
     "skewed_xtensor": 2154417468,
-    "mla_decode": 413566618,       # of which 86.9 MB are the partial results written
-    "mla_verify": 543842570,       # of which 171.7 MB written
+    "mla_decode": 370320991,       # of which 43.4 MB are the partial results written
+    "mla_verify": 442911683,       # of which 84.9 MB written
 }
 
 
