@@ -101,6 +101,11 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
  * out     DEVICE bf16 [batch, q_len, n_heads, d_latent];  lse DEVICE fp32 [batch, q_len, n_heads] or NULL
  * Supported: d_latent = 512, d_rope = 64, q_len * n_heads <= 4096, batch <= 4096; otherwise
  * XATTN_EUNSUPPORTED.  Same partition, workspace, stream, capture and ownership rules as xattn_decode.
+ * Numerics: fp32 accumulation; the softmax weights enter the value product as bf16 (see
+ * XATTN_CFG_PV_MODE); the partial output rows of a sequence that is split over several compute units
+ * pass through the workspace as fp16 scaled by the row's largest magnitude (11 significant bits per
+ * element).  q and the cached rows must be finite: an infinity or NaN makes the rows it reaches
+ * unspecified.
  */
 int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv_lens, int batch, int q_len,
                      int n_heads, int d_latent, int d_rope, float scale, void* out, float* lse, void* stream);
