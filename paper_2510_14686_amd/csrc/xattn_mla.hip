@@ -25,12 +25,16 @@
 //   * S^T = C Q^T: per 16-key tile 18 bf16 MFMA 16x16x32, the A operand (keys) read from LDS;
 //   * softmax on the accumulator layout: lane (kb, n) holds, of row n, the keys 4 kb + i of both key
 //     tiles, which is exactly the B operand (8 keys per lane) of the next product, so the weights
-//     never leave the lane; row maxima cross the four lane groups with lane-swap instructions;
+//     never leave the lane; row maxima cross the four lane groups with lane-swap instructions; the
+//     reference maximum of a row moves only when a block exceeds it by more than 2^8, so the 128
+//     accumulators are rescaled about once per segment instead of in most blocks;
 //   * O^T += C[:, 0:512]^T P^T: bf16 MFMA 16x16x32 over the 32 keys, the A operand (16 value columns x
 //     8 keys per lane) fetched with LDS transposing reads.  P goes in as one bf16 per weight and the
 //     output is normalised by the sum of those rounded weights; on request as hi + lo bf16 parts
 //     (two MFMAs, weights to 16 bits, normalised by the exact sum).
 // LDS reads are issued a few steps ahead of the MFMAs that use them, pinned with scheduling groups.
+// A segment that is not a whole sequence leaves its rows in the workspace as fp16, scaled by the
+// row's largest magnitude, with (m, l, lq, 1 / scale) in fp32; the merge kernel combines them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
