@@ -146,10 +146,12 @@ def run_workload(w, steps, warmup, check_rows, cpu_baseline, use_graph=False):
         if cpu_baseline:
             # The oracle as it stands on the host cores, over the sequences just checked.
             sel_tokens = int(lens[sel].sum())
-            reps = max(1, min(5, int(10.0 / max(t_or, 1e-3))))
+            # repeated until about 10 s of CPU work have been timed
+            reps = 0
             t0 = time.time()
-            for _ in range(reps):
+            while reps < 3 or (time.time() - t0 < 10.0 and reps < 1000):
                 oracle.attn(q[sel], [ks[b] for b in sel], [vs[b] for b in sel], lens[sel], w.scale)
+                reps += 1
             t_cpu = (time.time() - t0) / reps
             sel_bytes = sel_tokens * Hkv * D * 4
             res["cpu_baseline"] = {"value": sel_bytes / t_cpu / 1e9, "unit": "GB/s", "cores": oracle.num_threads(),
