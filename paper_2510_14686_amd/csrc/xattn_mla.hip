@@ -66,7 +66,7 @@ constexpr int kQSteps = kDqk / 32;               // 18 MFMA steps of 32 columns
 constexpr int kQRegSteps = 13;                   // Q columns 0 .. 32 * 13 - 1 stay in registers, the rest of Q in LDS
 constexpr int kQLdsWave = (kQSteps - kQRegSteps) * 1024;   // per 16-row tile: one 16-byte chunk per lane and step
 constexpr int kQAhead = 2;                       // key fragments in flight ahead of the MFMAs, in steps
-constexpr int kVAhead = 1;                       // value fragments in flight ahead of the MFMAs, in tile pairs
+constexpr int kVAhead = 2;                       // value fragments in flight ahead of the MFMAs, in tile pairs
 constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
 constexpr int kOutCols = 64;                     // epilogue: 16 rows x 64 fp32 columns at a time, padded
 constexpr int kOutPitch = kOutCols * 4 + 16;
