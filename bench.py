@@ -36,8 +36,8 @@ MEASURED_TRAFFIC_BYTES = {
     "long_context": 1628809212,
     "spec_verify": 2459629508,
     "skewed_xtensor": 2154417468,
-    "mla_decode": 370320991,       # of which 43.4 MB are the partial results written
-    "mla_verify": 442911683,       # of which 84.9 MB written
+    "mla_decode": 375470448,       # of which 47.0 MB are the partial results written
+    "mla_verify": 454308238,       # of which 92.2 MB written
 }
 
 
