@@ -61,8 +61,10 @@ const char* xattn_last_error(void);
  * kv_lens  DEVICE  int32[batch]; keys visible to the LAST new token, i.e. prefix + q_len (the new
  *                  tokens' K/V are already written).  Read on the device only.  A value < q_len
  *                  leaves the tokens without visible keys with out = 0 and lse = -inf.  The device
- *                  adds the lengths up in 32 bits: the sum over the batch of (kv_lens[b] + 128) must
- *                  stay below 2^31 (the host cannot check it; results are undefined beyond).
+ *                  adds the lengths up in 32 bits: the sum over the batch of (kv_lens[b] + 16) must
+ *                  stay below 2^31 (for xattn_mla_decode: kv_lens[b] + 192).  The host cannot check
+ *                  it and results are undefined beyond, but lengths whose caches fit one GPU's
+ *                  memory cannot reach it (2^31 rows of the smallest K/V row pair are 1 TiB).
  * batch    1..4096;  q_len 1..16;  head_dim must be 128;  n_q_heads a multiple of n_kv_heads;
  *          (n_q_heads / n_kv_heads) * q_len <= 64.  Otherwise XATTN_EUNSUPPORTED.
  * scale    multiplies the scores before the softmax (the caller's fp32 value, e.g. 1/sqrt(128))
@@ -73,13 +75,16 @@ const char* xattn_last_error(void);
  *
  * Graph capture (section 4.2, "Integrating Custom Operators"): the call may be recorded into a HIP
  * graph and replayed with other lengths, pointers and data in the same device buffers, since nothing
- * on the host depends on their values.  The workspace must be large enough beforehand (one eager call
- * of the shape, or xattn_set_workspace); a call that would have to grow it during capture returns
- * XATTN_ENOMEM and records nothing.
+ * on the host depends on their values.  The stream's workspace must be large enough beforehand (one
+ * eager call of the shape ON THAT STREAM, or xattn_set_workspace); a call that would have to grow it
+ * during capture returns XATTN_ENOMEM and records nothing.  A recorded graph stays valid when later
+ * calls grow the workspace: outgrown buffers are kept until the process ends, never freed.
  *
  * Ownership: the caller owns every buffer and keeps it alive and unmodified until the enqueued work
- * has finished.  The library's workspace (see below) is shared by all calls on a device, so calls
- * on different streams of one device must not overlap in time.  On failure nothing is enqueued.
+ * has finished.  The library keeps one workspace per stream (see below), so calls on different
+ * streams of a device may overlap; calls on ONE stream are ordered by the stream.  With a caller
+ * workspace (xattn_set_workspace) all streams share it and must not overlap.  On failure nothing is
+ * enqueued.
  */
 int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_ptrs,
                  const int32_t* kv_lens, int batch, int q_len, int n_q_heads, int n_kv_heads,
@@ -113,14 +118,21 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
 /*
  * Workspace for the partial results of split sequences (section 4.4.3: the parts of a split
  * sequence are computed by different compute units and aggregated afterwards).
- * xattn_workspace_bytes: upper bound on the bytes one xattn_decode call of this shape uses.
- * xattn_set_workspace:   hand the library a DEVICE buffer (256-byte aligned) for the current
- *                        device; the caller keeps ownership and keeps it alive while calls are in
- *                        flight.  (NULL, 0) returns to the library-owned workspace, which grows
- *                        with hipMalloc on the first call that needs more (that call synchronises
- *                        the device once to retire the old one).
+ * xattn_workspace_bytes:     upper bound on the bytes one xattn_decode call of this shape uses
+ *                            (0 and a message for an unsupported shape).
+ * xattn_mla_workspace_bytes: the same for one xattn_mla_decode call.
+ * xattn_set_workspace:       hand the library a DEVICE buffer (256-byte aligned) for the current
+ *                            device, used by calls on every stream; the caller keeps ownership and
+ *                            keeps it alive while calls are in flight or graphs that recorded them
+ *                            exist.  (NULL, 0) returns to the library-owned workspaces: one per
+ *                            stream (up to 64 streams per device), allocated with hipMalloc by the
+ *                            first call on the stream that needs more than it has.  An outgrown
+ *                            buffer is not freed before the process ends, because work in flight and
+ *                            recorded graphs may still use it; growth is geometric, so the outgrown
+ *                            buffers of a stream add up to less than four times its live one.
  */
 size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim);
+size_t xattn_mla_workspace_bytes(int batch, int q_len, int n_heads, int d_latent, int d_rope);
 int xattn_set_workspace(void* dev_ptr, size_t bytes);
 
 /*
@@ -247,17 +259,6 @@ int xtensor_premap_async(void* range, size_t mapped_bytes);
 int xtensor_premap_wait(void* range);
 int xtensor_close(void* range, int keep_reusable);
 int xtensor_range_pages(void* range, int64_t* page_ids_out, int n);
-
-/*
- * Testing hooks.  xtensor_test_fake_driver(1, fail_op, fail_after) replaces the HIP virtual-memory
- * calls under the page pool by a host-only stand-in (addresses from a counter, no memory behind
- * them), so that the pool's bookkeeping and its failure handling can be tested without a GPU;
- * fail_op (-1 none, 1 reserve, 3 create, 5 map, 6 unmap) fails once after fail_after successful
- * calls.  xtensor_test_fake_counts reports the stand-in's live reservations, pages and mappings.
- * Never enable in a process that runs kernels on pool memory.
- */
-int xtensor_test_fake_driver(int enable, int fail_op, int fail_after);
-int xtensor_test_fake_counts(size_t* reservations, size_t* handles, size_t* mappings);
 
 /*
  * write_kvcache (section 4.3, "Operator Adaptation": the operator that appends new tokens' K and V

@@ -4,8 +4,8 @@ from .binding import (XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_MLA_LAYOUT, XATTN_CF
                       xattn_workspace_bytes, xtensor_chunk_order, xtensor_download, xtensor_map,
                       xtensor_physical_view, xtensor_unmap, xtensor_upload)
 from .binding import (XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_FREE, XTENSOR_PAGE_MAPPED, XTENSOR_PAGE_REUSABLE,  # noqa: F401
-                      xattn_mla_decode, xattn_write_kvcache, xtensor_close, xtensor_grow, xtensor_open, xtensor_page_info,
+                      xattn_mla_decode, xattn_mla_workspace_bytes, xattn_write_kvcache, xtensor_close, xtensor_grow, xtensor_open, xtensor_page_info,
                       xtensor_pool_counts, xtensor_pool_create, xtensor_pool_destroy, xtensor_premap_async,
-                      xtensor_premap_wait, xtensor_range_pages, xtensor_test_fake_counts, xtensor_test_fake_driver)
+                      xtensor_premap_wait, xtensor_range_pages)
 from .binding import XBEAM_CHECK_INPUT, XBEAM_FULL_SORT, xbeam_select  # noqa: F401
 from .kvstore import KVStore  # noqa: F401

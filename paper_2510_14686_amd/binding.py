@@ -23,8 +23,7 @@ EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_s
            "xtensor_physical_view", "xtensor_upload", "xtensor_download",
            "xtensor_pool_create", "xtensor_pool_destroy", "xtensor_pool_counts", "xtensor_page_info",
            "xtensor_open", "xtensor_grow", "xtensor_premap_async", "xtensor_premap_wait", "xtensor_close",
-           "xtensor_range_pages", "xtensor_test_fake_driver", "xtensor_test_fake_counts", "xattn_write_kvcache",
-           "xattn_mla_decode", "xbeam_select"]
+           "xtensor_range_pages", "xattn_write_kvcache", "xattn_mla_decode", "xattn_mla_workspace_bytes", "xbeam_select"]
 XBEAM_FULL_SORT, XBEAM_CHECK_INPUT = 1, 2
 XTENSOR_PAGE_FREE, XTENSOR_PAGE_ALLOCATED, XTENSOR_PAGE_MAPPED, XTENSOR_PAGE_REUSABLE = 0, 1, 2, 3
 
@@ -38,6 +37,54 @@ class XattnError(RuntimeError):
 _lib = None
 
 
+def _signatures():
+    vp, i32, sz, u64, f32 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_float
+    P = ctypes.POINTER
+    return {
+        "xattn_last_error": (ctypes.c_char_p, []),
+        "xattn_decode": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp]),
+        "xattn_workspace_bytes": (sz, [i32] * 5),
+        "xattn_mla_workspace_bytes": (sz, [i32] * 5),
+        "xattn_set_workspace": (i32, [vp, sz]),
+        "xattn_configure": (i32, [i32, i32]),
+        "xattn_timing_read": (i32, [P(i32), P(f32), P(f32)]),
+        "xtensor_map": (i32, [sz, sz, u64, i32, P(vp), P(vp)]),
+        "xtensor_unmap": (i32, [vp]),
+        "xtensor_chunk_order": (i32, [vp, vp, i32]),
+        "xtensor_physical_view": (i32, [vp, P(vp)]),
+        "xtensor_upload": (i32, [vp, vp, sz]),
+        "xtensor_download": (i32, [vp, vp, sz]),
+        "xtensor_pool_create": (i32, [i32, sz, u64, P(vp)]),
+        "xtensor_pool_destroy": (i32, [vp]),
+        "xtensor_pool_counts": (i32, [vp, P(sz)]),
+        "xtensor_page_info": (i32, [vp, sz, P(i32), P(u64)]),
+        "xtensor_open": (i32, [vp, u64, sz, sz, P(vp), P(vp), P(i32)]),
+        "xtensor_grow": (i32, [vp, sz]),
+        "xtensor_premap_async": (i32, [vp, sz]),
+        "xtensor_premap_wait": (i32, [vp]),
+        "xtensor_close": (i32, [vp, i32]),
+        "xtensor_range_pages": (i32, [vp, vp, i32]),
+        "xattn_mla_decode": (i32, [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp]),
+        "xbeam_select": (i32, [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]),
+        "xattn_write_kvcache": (i32, [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]),
+    }
+
+
+def bind(lib: ctypes.CDLL, required=None) -> ctypes.CDLL:
+    """Set the C signatures on `lib` for every declared entry point it exports; the names in `required`
+    (default: all of EXPORTS) must be there."""
+    sigs = _signatures()
+    for name in (EXPORTS if required is None else required):
+        if not hasattr(lib, name):
+            raise AttributeError("%s does not export %s" % (lib._name, name))
+    for name, (restype, argtypes) in sigs.items():
+        if hasattr(lib, name):
+            fn = getattr(lib, name)
+            fn.restype = restype
+            fn.argtypes = argtypes
+    return lib
+
+
 def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     """Load libxattn.so (building it only if no built library exists)."""
     global _lib
@@ -48,63 +95,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         if p != _build.LIB_PATH:
             raise FileNotFoundError(p)
         p = _build.build()
-    lib = ctypes.CDLL(p)
-    vp, i32, sz, u64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint64
-    lib.xattn_last_error.restype = ctypes.c_char_p
-    lib.xattn_last_error.argtypes = []
-    lib.xattn_decode.restype = i32
-    lib.xattn_decode.argtypes = [vp, vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
-    lib.xattn_workspace_bytes.restype = sz
-    lib.xattn_workspace_bytes.argtypes = [i32] * 5
-    lib.xattn_set_workspace.restype = i32
-    lib.xattn_set_workspace.argtypes = [vp, sz]
-    lib.xattn_configure.restype = i32
-    lib.xattn_configure.argtypes = [i32, i32]
-    lib.xattn_timing_read.restype = i32
-    lib.xattn_timing_read.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_float),
-                                      ctypes.POINTER(ctypes.c_float)]
-    lib.xtensor_map.restype = i32
-    lib.xtensor_map.argtypes = [sz, sz, u64, i32, ctypes.POINTER(vp), ctypes.POINTER(vp)]
-    lib.xtensor_unmap.restype = i32
-    lib.xtensor_unmap.argtypes = [vp]
-    lib.xtensor_chunk_order.restype = i32
-    lib.xtensor_chunk_order.argtypes = [vp, vp, i32]
-    lib.xtensor_physical_view.restype = i32
-    lib.xtensor_physical_view.argtypes = [vp, ctypes.POINTER(vp)]
-    lib.xtensor_upload.restype = i32
-    lib.xtensor_upload.argtypes = [vp, vp, sz]
-    lib.xtensor_download.restype = i32
-    lib.xtensor_download.argtypes = [vp, vp, sz]
-    lib.xtensor_pool_create.restype = i32
-    lib.xtensor_pool_create.argtypes = [i32, sz, u64, ctypes.POINTER(vp)]
-    lib.xtensor_pool_destroy.restype = i32
-    lib.xtensor_pool_destroy.argtypes = [vp]
-    lib.xtensor_pool_counts.restype = i32
-    lib.xtensor_pool_counts.argtypes = [vp, ctypes.POINTER(sz)]
-    lib.xtensor_page_info.restype = i32
-    lib.xtensor_page_info.argtypes = [vp, sz, ctypes.POINTER(i32), ctypes.POINTER(u64)]
-    lib.xtensor_open.restype = i32
-    lib.xtensor_open.argtypes = [vp, u64, sz, sz, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i32)]
-    lib.xtensor_grow.restype = i32
-    lib.xtensor_grow.argtypes = [vp, sz]
-    lib.xtensor_premap_async.restype = i32
-    lib.xtensor_premap_async.argtypes = [vp, sz]
-    lib.xtensor_premap_wait.restype = i32
-    lib.xtensor_premap_wait.argtypes = [vp]
-    lib.xtensor_close.restype = i32
-    lib.xtensor_close.argtypes = [vp, i32]
-    lib.xtensor_range_pages.restype = i32
-    lib.xtensor_range_pages.argtypes = [vp, vp, i32]
-    lib.xtensor_test_fake_driver.restype = i32
-    lib.xtensor_test_fake_driver.argtypes = [i32, i32, i32]
-    lib.xtensor_test_fake_counts.restype = i32
-    lib.xtensor_test_fake_counts.argtypes = [ctypes.POINTER(sz)] * 3
-    lib.xattn_mla_decode.restype = i32
-    lib.xattn_mla_decode.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
-    lib.xbeam_select.restype = i32
-    lib.xbeam_select.argtypes = [vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
-    lib.xattn_write_kvcache.restype = i32
-    lib.xattn_write_kvcache.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, vp]
+    lib = bind(ctypes.CDLL(p))
     if path is None:
         _lib = lib
     return lib
@@ -142,6 +133,13 @@ def xattn_decode(q, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_q_heads: 
 
 def xattn_workspace_bytes(batch: int, q_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:
     n = int(load_library().xattn_workspace_bytes(batch, q_len, n_q_heads, n_kv_heads, head_dim))
+    if n == 0:
+        raise XattnError(XATTN_EUNSUPPORTED, xattn_last_error())
+    return n
+
+
+def xattn_mla_workspace_bytes(batch: int, q_len: int, n_heads: int, d_latent: int = 512, d_rope: int = 64) -> int:
+    n = int(load_library().xattn_mla_workspace_bytes(batch, q_len, n_heads, d_latent, d_rope))
     if n == 0:
         raise XattnError(XATTN_EUNSUPPORTED, xattn_last_error())
     return n
@@ -250,17 +248,6 @@ def xtensor_range_pages(rng: int) -> np.ndarray:
     buf = np.empty(1 << 16, dtype=np.int64)
     n = _check(load_library().xtensor_range_pages(rng, buf.ctypes.data, buf.size))
     return buf[:n].copy()
-
-
-def xtensor_test_fake_driver(enable: bool, fail_op: int = -1, fail_after: int = 0) -> None:
-    _check(load_library().xtensor_test_fake_driver(1 if enable else 0, fail_op, fail_after))
-
-
-def xtensor_test_fake_counts() -> Tuple[int, int, int]:
-    """(live reservations, live pages, live mappings) of the host-only stand-in driver."""
-    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    _check(load_library().xtensor_test_fake_counts(ctypes.byref(a), ctypes.byref(b), ctypes.byref(c)))
-    return int(a.value), int(b.value), int(c.value)
 
 
 def xattn_write_kvcache(k_new, v_new, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_kv_heads: int,

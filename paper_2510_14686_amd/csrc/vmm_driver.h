@@ -1,7 +1,8 @@
-// The five virtual-memory operations the xTensor page pool needs, behind one table, so that the
-// pool's bookkeeping and failure handling can run against a host-only stand-in (tests without a GPU)
-// as well as against the HIP virtual-memory API.  Every function returns an xattn_status and, on
-// failure, has recorded a message with fail()/fail_hip().
+// The virtual-memory operations the xTensor page pool needs, behind one table, so that the pool's
+// bookkeeping and failure handling can be built against a host-only stand-in (CPU tests, sanitizer
+// builds) as well as against the HIP virtual-memory API.  Every function returns an xattn_status
+// and, on failure, has recorded a message with fail().  Exactly one translation unit of a library
+// defines vmm_driver(): vmm_hip.cpp in libxattn.so, host_test/vmm_fake.cpp in the host test library.
 #ifndef XATTN_VMM_DRIVER_H_
 #define XATTN_VMM_DRIVER_H_
 
@@ -18,9 +19,9 @@ struct VmmDriver {
     int (*release)(uint64_t handle);
     int (*map)(void* va, size_t bytes, uint64_t handle, int device); // map and make read-write on device
     int (*unmap)(void* va, size_t bytes);
+    void (*bind_thread)(int device);                             // make `device` current for the calling thread
 };
 
-// The driver in use: HIP, or the host-only stand-in while xtensor_test_fake_driver is on.
 const VmmDriver& vmm_driver();
 
 }  // namespace xattn

@@ -2,31 +2,15 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
-#include <cstdarg>
-#include <cstdio>
 #include <mutex>
 #include <vector>
 
 #include "../../include/xattn.h"
-#include "xattn_internal.h"
+#include "xattn_hip_error.h"
+#include "xattn_host.h"
 #include "xattn_kernels.h"
 
 namespace xattn {
-
-static thread_local char g_error[512] = "";
-
-int fail(int status, const char* fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(g_error, sizeof(g_error), fmt, ap);
-    va_end(ap);
-    return status;
-}
-
-int fail_hip(hipError_t e, const char* what) {
-    const int status = (e == hipErrorOutOfMemory) ? XATTN_ENOMEM : XATTN_EHIP;
-    return fail(status, "%s failed: %s (%d)", what, hipGetErrorString(e), (int)e);
-}
 
 namespace {
 
@@ -36,11 +20,23 @@ constexpr int kMaxQLen = 16;
 constexpr int kMaxRows = 64;
 constexpr int kDefaultMinPieceTokens = 64;
 
+// The library's own workspaces: one per (device, stream), so that calls on different streams of a
+// device may overlap.  A buffer that has become too small is RETIRED, not freed: a HIP graph recorded
+// earlier may hold its address in the arguments of its kernel nodes, and replaying such a graph must
+// stay valid.  Buffers grow geometrically, so the retired ones add up to less than the live one
+// times four; all of them are released when the process ends.
+struct StreamWorkspace {
+    hipStream_t stream = nullptr;
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
+constexpr int kMaxStreamWorkspaces = 64;
+
 struct DeviceState {
     int n_cu = 0;
-    void* owned_ws = nullptr;    // library-owned workspace
-    size_t owned_bytes = 0;
-    void* user_ws = nullptr;     // caller-provided workspace, if any
+    std::vector<StreamWorkspace> owned;   // library-owned workspaces, one per stream seen
+    std::vector<void*> retired;           // outgrown buffers, kept alive (see above)
+    void* user_ws = nullptr;              // caller-provided workspace, if any: used for every stream
     size_t user_bytes = 0;
 };
 
@@ -76,6 +72,31 @@ WorkspaceLayout layout_for(int batch, int q_len, int n_q_heads, int n_pieces) {
     return w;
 }
 
+// Latent-KV call: per-sequence table, (m, l, lq, 1 / scale) per partial row, partial rows of 512 fp16.
+struct MlaWorkspaceLayout {
+    size_t ml_off, o_off, total;
+};
+MlaWorkspaceLayout mla_layout_for(int batch, int q_len, int n_heads, int n_pieces) {
+    const size_t slots = (size_t)n_pieces + (size_t)batch;
+    const size_t rows = (size_t)q_len * (size_t)n_heads;
+    MlaWorkspaceLayout w;
+    w.ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
+    w.o_off = w.ml_off + align_up(slots * rows * 4 * sizeof(float), 256);
+    w.total = w.o_off + align_up(slots * rows * 512 * sizeof(uint16_t), 256);
+    return w;
+}
+
+int check_mla_shape(int batch, int q_len, int n_heads, int d_latent, int d_rope) {
+    if (batch < 1 || q_len < 1 || n_heads < 1)
+        return fail(XATTN_EINVAL, "xattn_mla_decode: batch, q_len and n_heads must be positive");
+    if (d_latent != 512 || d_rope != 64)
+        return fail(XATTN_EUNSUPPORTED, "xattn_mla_decode: latent %d + rope %d: only 512 + 64 is supported", d_latent, d_rope);
+    if (batch > kMaxBatch) return fail(XATTN_EUNSUPPORTED, "batch %d exceeds %d", batch, kMaxBatch);
+    if (q_len > kMaxQLen) return fail(XATTN_EUNSUPPORTED, "q_len %d exceeds %d", q_len, kMaxQLen);
+    if ((long)q_len * n_heads > 4096) return fail(XATTN_EUNSUPPORTED, "q_len * n_heads = %ld exceeds 4096", (long)q_len * n_heads);
+    return XATTN_OK;
+}
+
 int check_shape(int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim) {
     if (batch < 1 || q_len < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1)
         return fail(XATTN_EINVAL, "batch, q_len, n_q_heads, n_kv_heads and head_dim must be positive");
@@ -107,8 +128,9 @@ int device_state(DeviceState** out, int* dev_out) {
     return XATTN_OK;
 }
 
-// The device's workspace of at least `total` bytes: the caller's if one was handed over, else the
-// library's own, grown when needed (never while `stream` is being captured).
+// A workspace of at least `total` bytes for a call on `stream`: the caller's if one was handed
+// over, else the library's own for that stream, grown when needed (never while `stream` is being
+// captured: growing allocates).
 int acquire_workspace(DeviceState* d, size_t total, hipStream_t stream, const char* who, char** ws_out) {
     if (d->user_ws) {
         if (d->user_bytes < total)
@@ -116,29 +138,33 @@ int acquire_workspace(DeviceState* d, size_t total, hipStream_t stream, const ch
         *ws_out = static_cast<char*>(d->user_ws);
         return XATTN_OK;
     }
-    if (d->owned_bytes < total) {
-        // Growing allocates and synchronises, which a stream under graph capture forbids.
+    StreamWorkspace* w = nullptr;
+    for (auto& cand : d->owned)
+        if (cand.stream == stream) w = &cand;
+    if (!w || w->bytes < total) {
         hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(stream, &capture) == hipSuccess && capture != hipStreamCaptureStatusNone)
             return fail(XATTN_ENOMEM,
-                        "%s: the workspace must grow to %zu bytes but the stream is being captured; "
-                        "run one call of this shape before the capture or hand over a workspace",
+                        "%s: this stream's workspace must grow to %zu bytes but the stream is being captured; "
+                        "run one call of this shape on the stream before the capture or hand over a workspace",
                         who, total);
-        // Work enqueued earlier may still use the old buffer: retire it before freeing.
-        hipError_t e = hipDeviceSynchronize();
-        if (e != hipSuccess) return fail_hip(e, "hipDeviceSynchronize");
-        if (d->owned_ws) (void)hipFree(d->owned_ws);
-        d->owned_ws = nullptr;
-        d->owned_bytes = 0;
-        const size_t want = total + total / 4;
-        e = hipMalloc(&d->owned_ws, want);
-        if (e != hipSuccess) {
-            d->owned_ws = nullptr;
-            return fail_hip(e, "hipMalloc(workspace)");
+        if (!w) {
+            if ((int)d->owned.size() >= kMaxStreamWorkspaces)
+                return fail(XATTN_ENOMEM, "%s: more than %d streams with a library-owned workspace on this device; "
+                                          "hand over a workspace with xattn_set_workspace", who, kMaxStreamWorkspaces);
+            d->owned.push_back(StreamWorkspace{stream, nullptr, 0});
+            w = &d->owned.back();
         }
-        d->owned_bytes = want;
+        const size_t want = total + total / 4;
+        void* fresh = nullptr;
+        const hipError_t e = hipMalloc(&fresh, want);
+        if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
+        // Work already enqueued, and graphs already recorded, keep using the old buffer.
+        if (w->ptr) d->retired.push_back(w->ptr);
+        w->ptr = fresh;
+        w->bytes = want;
     }
-    *ws_out = static_cast<char*>(d->owned_ws);
+    *ws_out = static_cast<char*>(w->ptr);
     return XATTN_OK;
 }
 
@@ -157,13 +183,71 @@ int timing_events(hipEvent_t** events_out) {
 }
 
 }  // namespace
+
+// xattn_decode and its variants: argument checks, workspace, launch.  `fixed_workspace`, when given,
+// supplies the workspace instead of the per-stream one (and the call is never timed: events allocate).
+int decode_call(const char* who, FixedWorkspaceFn fixed_workspace, const void* q, const void* const* k_ptrs,
+                const void* const* v_ptrs, const int32_t* kv_lens, int batch, int q_len, int n_q_heads,
+                int n_kv_heads, int head_dim, float scale, void* out, float* lse, void* stream) {
+    if (!q || !k_ptrs || !v_ptrs || !kv_lens || !out)
+        return fail(XATTN_EINVAL, "%s: q, k_ptrs, v_ptrs, kv_lens and out must not be NULL", who);
+    int st = check_shape(batch, q_len, n_q_heads, n_kv_heads, head_dim);
+    if (st != XATTN_OK) return st;
+    if (!std::isfinite(scale)) return fail(XATTN_EINVAL, "%s: scale is not finite", who);
+    if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
+        return fail(XATTN_EINVAL, "%s: q and out must be 16-byte aligned", who);
+
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState* d = nullptr;
+    int dev = 0;
+    st = device_state(&d, &dev);
+    if (st != XATTN_OK) return st;
+
+    const int n_pieces = pieces_for(d->n_cu);
+    const WorkspaceLayout w = layout_for(batch, q_len, n_q_heads, n_pieces);
+    char* ws = nullptr;
+    st = fixed_workspace ? fixed_workspace(who, dev, w.total, &ws)
+                         : acquire_workspace(d, w.total, static_cast<hipStream_t>(stream), who, &ws);
+    if (st != XATTN_OK) return st;
+
+    DecodeParams prm;
+    prm.q = static_cast<const uint16_t*>(q);
+    prm.k_ptrs = k_ptrs;
+    prm.v_ptrs = v_ptrs;
+    prm.kv_lens = kv_lens;
+    prm.batch = batch;
+    prm.q_len = q_len;
+    prm.n_q_heads = n_q_heads;
+    prm.n_kv_heads = n_kv_heads;
+    prm.group = n_q_heads / n_kv_heads;
+    prm.scale_log2 = (float)((double)scale * 1.4426950408889634074);
+    prm.out = static_cast<uint16_t*>(out);
+    prm.lse = lse;
+    prm.meta = reinterpret_cast<int32_t*>(ws + w.meta_off);
+    prm.part_ml = reinterpret_cast<float*>(ws + w.ml_off);
+    prm.part_o = reinterpret_cast<float*>(ws + w.o_off);
+    prm.n_pieces = n_pieces;
+    prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
+    if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;      // one 16-key block at least
+    prm.path = g_cfg_path;
+    prm.pv_mode = g_cfg_pv_mode;
+
+    hipEvent_t* events = nullptr;
+    if (!fixed_workspace) {
+        st = timing_events(&events);
+        if (st != XATTN_OK) return st;
+    }
+    hipError_t e = launch_decode(prm, static_cast<hipStream_t>(stream), events);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    if (events) ++g_timed_calls;
+    return XATTN_OK;
+}
+
 }  // namespace xattn
 
 using namespace xattn;
 
 extern "C" {
-
-const char* xattn_last_error(void) { return g_error; }
 
 int xattn_configure(int key, int value) {
     if (value < 0 || value > 65536) return fail(XATTN_EINVAL, "xattn_configure: value %d outside [0, 65536]", value);
@@ -197,6 +281,14 @@ size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads
     return layout_for(batch, q_len, n_q_heads, pieces).total;
 }
 
+size_t xattn_mla_workspace_bytes(int batch, int q_len, int n_heads, int d_latent, int d_rope) {
+    if (check_mla_shape(batch, q_len, n_heads, d_latent, d_rope) != XATTN_OK) return 0;
+    int pieces = g_cfg_pieces > 0 ? g_cfg_pieces : 256;
+    DeviceState* d = nullptr;
+    if (g_cfg_pieces == 0 && device_state(&d, nullptr) == XATTN_OK) pieces = pieces_for(d->n_cu);
+    return mla_layout_for(batch, q_len, n_heads, pieces).total;
+}
+
 int xattn_set_workspace(void* dev_ptr, size_t bytes) {
     if ((dev_ptr == nullptr) != (bytes == 0))
         return fail(XATTN_EINVAL, "xattn_set_workspace: pointer and size must both be given or both be zero");
@@ -214,54 +306,8 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes) {
 int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_ptrs, const int32_t* kv_lens,
                  int batch, int q_len, int n_q_heads, int n_kv_heads, int head_dim, float scale, void* out,
                  float* lse, void* stream) {
-    if (!q || !k_ptrs || !v_ptrs || !kv_lens || !out)
-        return fail(XATTN_EINVAL, "xattn_decode: q, k_ptrs, v_ptrs, kv_lens and out must not be NULL");
-    int st = check_shape(batch, q_len, n_q_heads, n_kv_heads, head_dim);
-    if (st != XATTN_OK) return st;
-    if (!std::isfinite(scale)) return fail(XATTN_EINVAL, "xattn_decode: scale is not finite");
-    if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
-        return fail(XATTN_EINVAL, "xattn_decode: q and out must be 16-byte aligned");
-
-    std::lock_guard<std::mutex> lock(g_mutex);
-    DeviceState* d = nullptr;
-    st = device_state(&d, nullptr);
-    if (st != XATTN_OK) return st;
-
-    const int n_pieces = pieces_for(d->n_cu);
-    const WorkspaceLayout w = layout_for(batch, q_len, n_q_heads, n_pieces);
-    char* ws = nullptr;
-    st = acquire_workspace(d, w.total, static_cast<hipStream_t>(stream), "xattn_decode", &ws);
-    if (st != XATTN_OK) return st;
-
-    DecodeParams prm;
-    prm.q = static_cast<const uint16_t*>(q);
-    prm.k_ptrs = k_ptrs;
-    prm.v_ptrs = v_ptrs;
-    prm.kv_lens = kv_lens;
-    prm.batch = batch;
-    prm.q_len = q_len;
-    prm.n_q_heads = n_q_heads;
-    prm.n_kv_heads = n_kv_heads;
-    prm.group = n_q_heads / n_kv_heads;
-    prm.scale_log2 = (float)((double)scale * 1.4426950408889634074);
-    prm.out = static_cast<uint16_t*>(out);
-    prm.lse = lse;
-    prm.meta = reinterpret_cast<int32_t*>(ws + w.meta_off);
-    prm.part_ml = reinterpret_cast<float*>(ws + w.ml_off);
-    prm.part_o = reinterpret_cast<float*>(ws + w.o_off);
-    prm.n_pieces = n_pieces;
-    prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
-    if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;      // one 16-key block at least
-    prm.path = g_cfg_path;
-    prm.pv_mode = g_cfg_pv_mode;
-
-    hipEvent_t* events = nullptr;
-    st = timing_events(&events);
-    if (st != XATTN_OK) return st;
-    hipError_t e = launch_decode(prm, static_cast<hipStream_t>(stream), events);
-    if (e != hipSuccess) return fail_hip(e, "kernel launch");
-    if (events) ++g_timed_calls;
-    return XATTN_OK;
+    return decode_call("xattn_decode", nullptr, q, k_ptrs, v_ptrs, kv_lens, batch, q_len, n_q_heads, n_kv_heads,
+                       head_dim, scale, out, lse, stream);
 }
 
 int xattn_timing_read(int* n_calls, float* decode_kernel_ms, float* merge_kernel_ms) {
@@ -289,30 +335,20 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
                      int n_heads, int d_latent, int d_rope, float scale, void* out, float* lse, void* stream) {
     if (!q || !c_ptrs || !kv_lens || !out)
         return fail(XATTN_EINVAL, "xattn_mla_decode: q, c_ptrs, kv_lens and out must not be NULL");
-    if (batch < 1 || q_len < 1 || n_heads < 1)
-        return fail(XATTN_EINVAL, "xattn_mla_decode: batch, q_len and n_heads must be positive");
-    if (d_latent != 512 || d_rope != 64)
-        return fail(XATTN_EUNSUPPORTED, "xattn_mla_decode: latent %d + rope %d: only 512 + 64 is supported", d_latent, d_rope);
-    if (batch > kMaxBatch) return fail(XATTN_EUNSUPPORTED, "batch %d exceeds %d", batch, kMaxBatch);
-    if (q_len > kMaxQLen) return fail(XATTN_EUNSUPPORTED, "q_len %d exceeds %d", q_len, kMaxQLen);
-    if ((long)q_len * n_heads > 4096) return fail(XATTN_EUNSUPPORTED, "q_len * n_heads = %ld exceeds 4096", (long)q_len * n_heads);
+    int st = check_mla_shape(batch, q_len, n_heads, d_latent, d_rope);
+    if (st != XATTN_OK) return st;
     if (!std::isfinite(scale) || !(scale > 0.0f)) return fail(XATTN_EINVAL, "xattn_mla_decode: scale %g is not a positive finite number", (double)scale);
     if (reinterpret_cast<uintptr_t>(q) % 16 != 0 || reinterpret_cast<uintptr_t>(out) % 16 != 0)
         return fail(XATTN_EINVAL, "xattn_mla_decode: q and out must be 16-byte aligned");
 
     std::lock_guard<std::mutex> lock(g_mutex);
     DeviceState* d = nullptr;
-    int st = device_state(&d, nullptr);
+    st = device_state(&d, nullptr);
     if (st != XATTN_OK) return st;
     const int n_pieces = pieces_for(d->n_cu);
-    // per-sequence table, partial (m, l, lq, 1 / scale) per row, partial rows of 512 fp16
-    const size_t slots = (size_t)n_pieces + (size_t)batch;
-    const size_t rows = (size_t)q_len * (size_t)n_heads;
-    const size_t ml_off = align_up((size_t)batch * 2 * sizeof(int32_t), 256);
-    const size_t o_off = ml_off + align_up(slots * rows * 4 * sizeof(float), 256);      // (m, l, lq, 1 / scale) per partial row
-    const size_t total = o_off + align_up(slots * rows * 512 * sizeof(uint16_t), 256);
+    const MlaWorkspaceLayout w = mla_layout_for(batch, q_len, n_heads, n_pieces);
     char* ws = nullptr;
-    st = acquire_workspace(d, total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);
+    st = acquire_workspace(d, w.total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);
     if (st != XATTN_OK) return st;
 
     MlaParams prm;
@@ -326,8 +362,8 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.out = static_cast<uint16_t*>(out);
     prm.lse = lse;
     prm.meta = reinterpret_cast<int32_t*>(ws);
-    prm.part_ml = reinterpret_cast<float*>(ws + ml_off);
-    prm.part_o = reinterpret_cast<uint16_t*>(ws + o_off);
+    prm.part_ml = reinterpret_cast<float*>(ws + w.ml_off);
+    prm.part_o = reinterpret_cast<uint16_t*>(ws + w.o_off);
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;

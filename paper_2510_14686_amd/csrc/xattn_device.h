@@ -7,6 +7,7 @@
 #include <stdint.h>
 
 #include "xattn_kernels.h"
+#include "xattn_plan.h"
 
 namespace xattn {
 namespace {
@@ -93,53 +94,94 @@ __device__ __forceinline__ void store_b128(void* base, uint32_t bytes, uint32_t 
 }
 
 // ---------------------------------------------------------------------------------- the plan
-// All keys of the batch form one stream that is cut into pieces of equal COST.  A sequence of L > 0
-// tokens occupies L + seg_cost positions of the stream: its tokens, then seg_cost positions that stand
-// for the fixed work every (piece, sequence) segment costs (first loads, Q, the stores of its result),
-// so a workgroup whose piece spans a sequence boundary gets correspondingly fewer tokens.  A piece
-// bound that falls into those extra positions means "the end of that sequence".  seg_cost = 0 gives
-// pieces of equal token count.
-struct Plan {
-    int total;      // N: positions of the whole stream
-    int n_pieces;   // pieces in use: min(launched pieces, N / minimum piece size), at least 1
-    int seg_cost;
+// Wave-level front end of the partition in xattn_plan.h.  Every wave computes the plan itself from
+// kv_lens (the host never reads the lengths: section 4.2, "Integrating Custom Operators"), in two
+// memory round trips and two wave scans whatever the batch: lane l owns the `chunk` consecutive
+// sequences l * chunk .. l * chunk + chunk - 1 (chunk = the power of two >= batch / 64, so at most 64
+// for the largest batch) and adds up their stream positions from 128-bit loads that are all in
+// flight together; one scan over the 64 lane sums gives the total and every chunk's first position;
+// a stream position is then located by one ballot (its chunk) and one scan over that chunk's
+// sequences.  The loads go through a buffer descriptor over kv_lens, so indices past the batch read 0.
+struct WavePlan {
+    Plan pl;
+    int chunk, chunk_log2;   // sequences per lane
+    int mine;                // stream positions of this lane's sequences
+    int excl;                // stream positions before this lane's first sequence
 };
 
-__device__ __forceinline__ int clamp_len(int v) { return v > 0 ? v : 0; }
-// Stream positions of a sequence of `len` tokens (any sign).
-__device__ __forceinline__ int stream_len(int len, int seg_cost) { return len > 0 ? len + seg_cost : 0; }
+template <int kQuads>
+__device__ __forceinline__ int chunk_positions(__amdgpu_buffer_rsrc_t rl, int first, int seg_cost) {
+    u32x4_t v[kQuads];
+#pragma unroll
+    for (int k = 0; k < kQuads; ++k) v[k] = __builtin_amdgcn_raw_buffer_load_b128(rl, (first + 4 * k) * 4, 0, 0);
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kQuads; ++k)
+        sum += stream_len((int)v[k].x, seg_cost) + stream_len((int)v[k].y, seg_cost) +
+               stream_len((int)v[k].z, seg_cost) + stream_len((int)v[k].w, seg_cost);
+    return sum;
+}
 
-__device__ __forceinline__ Plan make_plan(const int32_t* __restrict__ kv_lens, int batch, int n_pieces,
-                                          int min_piece, int seg_cost, int lane) {
-    int total = 0;
-    for (int base = 0; base < batch; base += 64) {
-        const int i = base + lane;
-        total += wave_sum_i(i < batch ? stream_len(kv_lens[i], seg_cost) : 0);
+__device__ __forceinline__ WavePlan wave_plan(const int32_t* __restrict__ kv_lens, int batch, int n_pieces,
+                                              int min_piece, int seg_cost, int lane) {
+    WavePlan wp;
+    int lg = 0;
+    while ((64 << lg) < batch) ++lg;                       // wave-uniform: batch is a kernel argument
+    wp.chunk_log2 = lg;
+    wp.chunk = 1 << lg;
+    const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
+    const int first = lane << lg;
+    int mine;
+    switch (lg) {
+        case 0: mine = stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4, 0, 0), seg_cost); break;
+        case 1: mine = stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4, 0, 0), seg_cost) +
+                       stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4 + 4, 0, 0), seg_cost); break;
+        case 2: mine = chunk_positions<1>(rl, first, seg_cost); break;
+        case 3: mine = chunk_positions<2>(rl, first, seg_cost); break;
+        case 4: mine = chunk_positions<4>(rl, first, seg_cost); break;
+        case 5: mine = chunk_positions<8>(rl, first, seg_cost); break;
+        default: mine = chunk_positions<16>(rl, first, seg_cost); break;   // batch <= 4096 (checked by the host)
     }
-    total = __builtin_amdgcn_readfirstlane(total);
-    int n = total / min_piece;
-    n = n < 1 ? 1 : n;
-    Plan pl;
-    pl.total = total;
-    pl.n_pieces = n < n_pieces ? n : n_pieces;
-    pl.seg_cost = seg_cost;
-    return pl;
+    const int incl = wave_incl_scan_i(mine, lane);
+    wp.mine = mine;
+    wp.excl = incl - mine;
+    wp.pl = plan_for_total(__builtin_amdgcn_readlane(incl, 63), n_pieces, min_piece, seg_cost);
+    return wp;
 }
 
-// Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): p * N / n_pieces rounded to a
-// multiple of the 16-key block, so every piece is within 16 positions of N / n_pieces and all are used.
-__device__ __forceinline__ int piece_bound(const Plan& pl, int p) {
-    if (p >= pl.n_pieces) return pl.total;
-    const long x = (long)p * pl.total / pl.n_pieces;
-    const int r = (int)((x + kBlockKeys / 2) / kBlockKeys) * kBlockKeys;
-    return r < pl.total ? r : pl.total;
+// The sequence b that holds stream position s (0 <= s < N) and the offset j of s within that
+// sequence's L + seg_cost positions.  Both wave-uniform.
+__device__ __forceinline__ void wave_locate(const WavePlan& wp, const int32_t* __restrict__ kv_lens, int batch, int s,
+                                            int lane, int& b, int& j) {
+    const unsigned long long hit = __ballot(s >= wp.excl && s < wp.excl + wp.mine);
+    const int ln = hit ? __builtin_ctzll(hit) : 0;
+    const int base = ln << wp.chunk_log2;
+    const int off = s - __shfl(wp.excl, ln, 64);
+    const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
+    const int v = lane < wp.chunk ? stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, (base + lane) * 4, 0, 0), wp.pl.seg_cost) : 0;
+    const int incl = wave_incl_scan_i(v, lane);
+    const unsigned long long hit2 = __ballot(off >= incl - v && off < incl);
+    const int ln2 = hit2 ? __builtin_ctzll(hit2) : 0;
+    b = __builtin_amdgcn_readfirstlane(base + ln2);
+    j = __builtin_amdgcn_readfirstlane(off - __shfl(incl - v, ln2, 64));
 }
-// The piece that owns stream position x (0 <= x < N).
-__device__ __forceinline__ int piece_of(const Plan& pl, int x) {
-    int p = (int)((long)x * pl.n_pieces / pl.total);
-    while (p + 1 < pl.n_pieces && piece_bound(pl, p + 1) <= x) ++p;
-    while (p > 0 && piece_bound(pl, p) > x) --p;
-    return p;
+
+// For the merge kernel: (first partial slot, number of segments) of sequences 64 g .. 64 g + 63, one
+// per lane.  A group of 64 sequences holds 64 / chunk whole chunks; a sequence's first position is its
+// chunk's first position plus the positions of the chunk's earlier sequences.
+__device__ __forceinline__ void wave_write_meta(const WavePlan& wp, const int32_t* __restrict__ kv_lens, int batch, int g,
+                                                int lane, int32_t* __restrict__ meta) {
+    const int seq = 64 * g + lane;
+    const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
+    const int len = clamp_len(__builtin_amdgcn_raw_buffer_load_b32(rl, seq * 4, 0, 0));
+    const int v = stream_len(len, wp.pl.seg_cost);
+    const int before = wave_incl_scan_i(v, lane) - v;                       // within the group
+    const int chunk_first = __shfl(wp.excl, (seq >> wp.chunk_log2) & 63, 64);
+    const int start = chunk_first + before - __shfl(before, lane & ~(wp.chunk - 1), 64);
+    if (seq < batch) {
+        const SeqMeta m = seq_meta(wp.pl, seq, start, len);
+        reinterpret_cast<int2*>(meta)[seq] = make_int2(m.first_slot, m.n_seg);
+    }
 }
 
 }  // namespace

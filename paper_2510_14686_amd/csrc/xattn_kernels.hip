@@ -516,7 +516,8 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     const int wave = threadIdx.x >> 6;
     const int kvh = blockIdx.z * kMaxWavesPerBlock + wave;
     if (kvh >= prm.n_kv_heads) return;
-    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kGqaSegCost, lane);
+    const WavePlan wp = wave_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kGqaSegCost, lane);
+    const Plan& pl = wp.pl;
 
     // Piece index: consecutive workgroups go to different XCDs, so give each XCD one contiguous
     // eighth of the token stream.
@@ -526,88 +527,48 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     const int s0 = piece_bound(pl, p), s1 = piece_bound(pl, p + 1);
     const bool active = (bid >> 3) < per_xcd && p < pl.n_pieces && s0 < s1;
 
-    if (bid == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64) {
-        // For the merge kernel: first partial slot and number of segments of every sequence.
-        int run = 0;
-        for (int base = 0; base < prm.batch; base += 64) {
-            const int i = base + lane;
-            const int len = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
-            const int v = stream_len(len, pl.seg_cost);
-            const int incl = wave_incl_scan_i(v, lane) + run;
-            if (i < prm.batch) {
-                // the pieces from the one with the sequence's first token to the one with its last
-                const int first = len > 0 ? piece_of(pl, incl - v) : 0;
-                const int n_seg = len > 0 ? piece_of(pl, incl - v + len - 1) - first + 1 : 0;
-                reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
-            }
-            run = __shfl(incl, 63, 64);
-        }
+    if (blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64) {
+        // For the merge kernel: first partial slot and number of segments of every sequence, 64
+        // sequences per wave, the groups of 64 dealt out over the workgroups.
+        for (int g = bid; 64 * g < prm.batch; g += gridDim.x) wave_write_meta(wp, prm.kv_lens, prm.batch, g, lane, prm.meta);
     }
     if (!active) return;
 
-
-    // Locate the sequence that holds stream position s0; j = offset within its L + seg_cost positions.
-    int b = 0, j = 0;
-    {
-        int run = 0;
-        for (int base = 0; base < prm.batch; base += 64) {
-            const int i = base + lane;
-            const int v = i < prm.batch ? stream_len(prm.kv_lens[i], pl.seg_cost) : 0;
-            const int incl = wave_incl_scan_i(v, lane) + run;
-            const unsigned long long hit = __ballot(s0 >= incl - v && s0 < incl);
-            if (hit) {
-                const int ln = __builtin_ctzll(hit);
-                b = base + ln;
-                j = s0 - __shfl(incl - v, ln, 64);
-                break;
-            }
-            run = __shfl(incl, 63, 64);
-        }
-        b = __builtin_amdgcn_readfirstlane(b);
-        j = __builtin_amdgcn_readfirstlane(j);
-    }
+    Walk walk;
+    wave_locate(wp, prm.kv_lens, prm.batch, s0, lane, walk.b, walk.j);
+    walk.remaining = s1 - s0;
 
     const int rows_total = prm.group * prm.q_len;
     Segment seg;
     seg.kvh = kvh;
     seg.row0 = blockIdx.y * R;
     seg.n_rows = rows_total - seg.row0 < R ? rows_total - seg.row0 : R;
-    int remaining = s1 - s0;            // stream positions left in this piece
     // Next (piece, sequence) intersection of this piece, in stream order; false when the piece is done.
-    auto next_segment = [&](Segment& out) {
-        while (remaining > 0 && b < prm.batch) {
-            const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
-            if (L == 0) { ++b; continue; }
-            // the piece's share of this sequence's L + seg_cost positions, and the tokens among them
-            const int n_pos = (L + pl.seg_cost - j < remaining) ? L + pl.seg_cost - j : remaining;
-            const int j0 = j < L ? j : L, j1 = j + n_pos < L ? j + n_pos : L;
-            remaining -= n_pos;
-            const int bb = b;
-            ++b;
-            j = 0;
-            if (j1 <= j0) continue;                    // only the sequence's extra positions: no tokens
-            out = seg;
-            out.b = bb;
-            out.L = L;
-            out.j0 = j0;
-            out.j1 = j1;
-            out.slot = p + bb;
-            out.whole = (j0 == 0 && j1 == L);
-            return true;
-        }
-        return false;
+    auto next_seg = [&](Segment& out) {
+        PieceSeg ps;
+        if (!next_segment(walk, prm.batch, pl.seg_cost,
+                          [&](int b) { return __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b])); }, ps))
+            return false;
+        out = seg;
+        out.b = ps.b;
+        out.L = ps.L;
+        out.j0 = ps.j0;
+        out.j1 = ps.j1;
+        out.slot = p + ps.b;
+        out.whole = ps.whole;
+        return true;
     };
     if (kMatrix) {
         char* lds_wave = lds + wave * kLdsPerWave;
         Segment cur_seg;
-        if (!next_segment(cur_seg)) return;
+        if (!next_seg(cur_seg)) return;
         MatrixCtx cur;
         matrix_begin(cur, prm, cur_seg, lane);
         for (;;) {
             MatrixState st;
             matrix_run<kPv>(st, cur, prm, lane, lds_wave);
             Segment nxt_seg;
-            const bool more = next_segment(nxt_seg);
+            const bool more = next_seg(nxt_seg);
             MatrixCtx nxt;
             if (more) matrix_begin(nxt, prm, nxt_seg, lane);     // its loads go out before cur's stores
             if (more) matrix_finish<true>(st, cur, prm, lane, lds_wave);
@@ -617,7 +578,7 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
         }
     } else {
         Segment s2;
-        while (next_segment(s2)) vector_segment<R>(prm, s2, lane);
+        while (next_seg(s2)) vector_segment<R>(prm, s2, lane);
     }
 }
 

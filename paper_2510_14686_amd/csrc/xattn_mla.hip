@@ -92,7 +92,7 @@ struct MlaTile {
 // before each read.  dma_wait() before the workgroup barrier is what makes a block visible.
 __device__ __forceinline__ void dma16(u32x4_t rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 1\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
 }
 // Waits until at most n of this wave's loads are outstanding (they complete in order): n = the number
 // of loads of the newest block leaves the block before it complete.
@@ -365,7 +365,8 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 4, n = lane & 15;
     const int T = prm.q_len, H = prm.n_heads, rows_total = T * H;
-    const Plan pl = make_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kMlaSegCost, lane);
+    const WavePlan wp = wave_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kMlaSegCost, lane);
+    const Plan& pl = wp.pl;
     const int per_xcd = (pl.n_pieces + 7) >> 3;
     // Workgroup ids go round-robin over the 8 XCDs.  Of an XCD's workgroups, consecutive ones are the
     // row groups of one piece: they run at the same time on the same XCD and share its L2, so the
@@ -378,45 +379,16 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     const int s0 = piece_bound(pl, p), s1 = piece_bound(pl, p + 1);
     const bool active = slot_in_xcd / n_groups < per_xcd && p < pl.n_pieces && s0 < s1;
 
-    if (bid == 0 && tid < 64) {
-        // For the merge kernel: first partial slot and number of segments of every sequence.
-        int run = 0;
-        for (int base = 0; base < prm.batch; base += 64) {
-            const int i = base + lane;
-            const int len = i < prm.batch ? clamp_len(prm.kv_lens[i]) : 0;
-            const int v = stream_len(len, pl.seg_cost);
-            const int incl = wave_incl_scan_i(v, lane) + run;
-            if (i < prm.batch) {
-                // the pieces from the one with the sequence's first token to the one with its last
-                const int first = len > 0 ? piece_of(pl, incl - v) : 0;
-                const int n_seg = len > 0 ? piece_of(pl, incl - v + len - 1) - first + 1 : 0;
-                reinterpret_cast<int2*>(prm.meta)[i] = make_int2(first + i, n_seg);
-            }
-            run = __shfl(incl, 63, 64);
-        }
+    if (tid < 64) {
+        // For the merge kernel: first partial slot and number of segments of every sequence, 64
+        // sequences per wave, the groups of 64 dealt out over the workgroups.
+        for (int g = bid; 64 * g < prm.batch; g += gridDim.x) wave_write_meta(wp, prm.kv_lens, prm.batch, g, lane, prm.meta);
     }
     if (!active) return;       // the whole workgroup: every wave computed the same plan
 
-    // Locate the sequence that holds stream position s0; j = offset within its L + seg_cost positions.
-    int b = 0, j = 0;
-    {
-        int run = 0;
-        for (int base = 0; base < prm.batch; base += 64) {
-            const int i = base + lane;
-            const int v = i < prm.batch ? stream_len(prm.kv_lens[i], pl.seg_cost) : 0;
-            const int incl = wave_incl_scan_i(v, lane) + run;
-            const unsigned long long hit = __ballot(s0 >= incl - v && s0 < incl);
-            if (hit) {
-                const int ln = __builtin_ctzll(hit);
-                b = base + ln;
-                j = s0 - __shfl(incl - v, ln, 64);
-                break;
-            }
-            run = __shfl(incl, 63, 64);
-        }
-        b = __builtin_amdgcn_readfirstlane(b);
-        j = __builtin_amdgcn_readfirstlane(j);
-    }
+    Walk walk;
+    wave_locate(wp, prm.kv_lens, prm.batch, s0, lane, walk.b, walk.j);
+    walk.remaining = s1 - s0;
 
     // Row n of tile rt of this wave: row index within the sequence's T * H rows.
     const int wave_row0 = row_group * (16 * RT * NW) + wave * (16 * RT);
@@ -433,16 +405,11 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    int remaining = s1 - s0;            // stream positions left in this piece
-    while (remaining > 0 && b < prm.batch) {
-        const int L = __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[b]));
-        if (L == 0) { ++b; continue; }
-        // the piece's share of this sequence's L + seg_cost positions, and the tokens among them
-        const int n_pos = (L + pl.seg_cost - j < remaining) ? L + pl.seg_cost - j : remaining;
-        const int j0 = j < L ? j : L, j1 = j + n_pos < L ? j + n_pos : L;
-        remaining -= n_pos;
-        if (j1 <= j0) { ++b; j = 0; continue; }       // only the sequence's extra positions: no tokens
-        const bool whole = (j0 == 0 && j1 == L);
+    PieceSeg ps;
+    while (next_segment(walk, prm.batch, pl.seg_cost,
+                        [&](int bb) { return __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[bb])); }, ps)) {
+        const int b = ps.b, L = ps.L, j0 = ps.j0, j1 = ps.j1;
+        const bool whole = ps.whole;
         const long slot = (long)p + b;
         const unsigned long long cbytes = (unsigned long long)L * kRowB;
         const uint64_t caddr = (uint64_t)(uintptr_t)prm.c_ptrs[b];
@@ -566,8 +533,6 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 }
             }
         }
-        ++b;
-        j = 0;
     }
 }
 

@@ -1,0 +1,124 @@
+// The token-stream partition of the decode kernels (paper section 4.4.3, "Layer 3": balance compute
+// units by token count, split long sequences, let short ones share a unit) as plain integer code that
+// compiles for the device and for the host: the kernels use it through the wave-level front end in
+// xattn_device.h, the CPU property tests through host_test/plan_shim.cpp.
+//
+// All keys of the batch form one stream that is cut into pieces of equal COST.  A sequence of L > 0
+// tokens occupies L + seg_cost positions of the stream: its tokens, then seg_cost positions that stand
+// for the fixed work every (piece, sequence) segment costs (first loads, Q, the stores of its result),
+// so a workgroup whose piece spans a sequence boundary gets correspondingly fewer tokens.  A piece
+// bound that falls into those extra positions means "the end of that sequence".  seg_cost = 0 gives
+// pieces of equal token count.  Sequences without tokens occupy no positions.
+//
+// Limits: stream positions are 32-bit.  N = sum_b (L_b + seg_cost) must stay below 2^31, which the
+// memory of one GPU guarantees for real caches (2^31 tokens of the smallest supported row, 256 bytes
+// of K plus 256 of V, are 1 TiB); n_pieces <= 65536.
+#ifndef XATTN_PLAN_H_
+#define XATTN_PLAN_H_
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define XATTN_HD __host__ __device__ __forceinline__
+#else
+#define XATTN_HD inline
+#endif
+
+namespace xattn {
+
+constexpr int kPlanRound = 16;        // piece bounds are multiples of the 16-key block (except the last)
+constexpr int kMaxPieces = 65536;
+
+struct Plan {
+    int total;      // N: positions of the whole stream
+    int n_pieces;   // pieces in use: min(launched pieces, N / minimum piece size), at least 1
+    int seg_cost;
+};
+
+XATTN_HD int clamp_len(int v) { return v > 0 ? v : 0; }
+// Stream positions of a sequence of `len` tokens (any sign).
+XATTN_HD int stream_len(int len, int seg_cost) { return len > 0 ? len + seg_cost : 0; }
+
+XATTN_HD Plan plan_for_total(int total, int n_pieces, int min_piece, int seg_cost) {
+    int n = total / (min_piece > 0 ? min_piece : 1);
+    n = n < 1 ? 1 : n;
+    Plan pl;
+    pl.total = total;
+    pl.n_pieces = n < n_pieces ? n : n_pieces;
+    pl.seg_cost = seg_cost;
+    return pl;
+}
+
+// Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): floor(p * N / n_pieces) rounded
+// to the nearest multiple of the 16-key block, so every piece is within 16 positions of N / n_pieces
+// and all are used.  32-bit arithmetic only: p * N / n = p * (N / n) + p * (N % n) / n, and
+// p * (N % n) < n^2 <= 2^32.
+XATTN_HD int piece_bound(const Plan& pl, int p) {
+    if (p >= pl.n_pieces) return pl.total;
+    const uint32_t n = (uint32_t)pl.n_pieces, q = (uint32_t)pl.total / n, r = (uint32_t)pl.total % n;
+    const uint32_t x = (uint32_t)p * q + (uint32_t)p * r / n;
+    const uint32_t rounded = (x + kPlanRound / 2) / kPlanRound * kPlanRound;
+    return rounded < (uint32_t)pl.total ? (int)rounded : pl.total;
+}
+
+// The piece that owns stream position x (0 <= x < N): an estimate, corrected against piece_bound.
+XATTN_HD int piece_of(const Plan& pl, int x) {
+    int p = (int)((float)x * (float)pl.n_pieces / (float)pl.total);
+    p = p < 0 ? 0 : (p > pl.n_pieces - 1 ? pl.n_pieces - 1 : p);
+    while (p + 1 < pl.n_pieces && piece_bound(pl, p + 1) <= x) ++p;
+    while (p > 0 && piece_bound(pl, p) > x) --p;
+    return p;
+}
+
+// What the merge kernel needs to know of a sequence that starts at stream position `start` and has
+// `len` tokens: its first partial-result slot and its number of (piece, sequence) segments, i.e. the
+// pieces from the one with its first token to the one with its last.  Slot of a segment = piece +
+// sequence index (unique: piece and sequence index never both stand still between two segments).
+struct SeqMeta { int first_slot, n_seg; };
+XATTN_HD SeqMeta seq_meta(const Plan& pl, int b, int start, int len) {
+    SeqMeta m;
+    if (len <= 0) { m.first_slot = b; m.n_seg = 0; return m; }
+    const int first = piece_of(pl, start);
+    m.first_slot = first + b;
+    m.n_seg = piece_of(pl, start + len - 1) - first + 1;
+    return m;
+}
+
+// A piece's walk over the sequences it intersects, in stream order.
+struct Walk {
+    int b;            // next sequence to look at
+    int j;            // offset into that sequence's L + seg_cost positions
+    int remaining;    // stream positions left in the piece
+};
+struct PieceSeg {
+    int b, L;         // sequence and its length
+    int j0, j1;       // tokens [j0, j1) of it
+    bool whole;       // the segment is the whole sequence: no partial result, no merge
+};
+// len_of(b) returns clamp_len(kv_lens[b]).  Returns false when the piece is exhausted.
+template <typename LenFn>
+XATTN_HD bool next_segment(Walk& w, int batch, int seg_cost, LenFn len_of, PieceSeg& out) {
+    while (w.remaining > 0 && w.b < batch) {
+        const int L = len_of(w.b);
+        if (L == 0) { ++w.b; continue; }
+        // the piece's share of this sequence's L + seg_cost positions, and the tokens among them
+        const int left = L + seg_cost - w.j;
+        const int n_pos = left < w.remaining ? left : w.remaining;
+        const int j0 = w.j < L ? w.j : L, j1 = w.j + n_pos < L ? w.j + n_pos : L;
+        w.remaining -= n_pos;
+        const int bb = w.b;
+        ++w.b;
+        w.j = 0;
+        if (j1 <= j0) continue;                    // only the sequence's extra positions: no tokens
+        out.b = bb;
+        out.L = L;
+        out.j0 = j0;
+        out.j1 = j1;
+        out.whole = (j0 == 0 && j1 == L);
+        return true;
+    }
+    return false;
+}
+
+}  // namespace xattn
+#endif

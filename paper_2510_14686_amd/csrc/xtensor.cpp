@@ -10,7 +10,7 @@
 #include <vector>
 
 #include "../../include/xattn.h"
-#include "xattn_internal.h"
+#include "xattn_hip_error.h"
 
 namespace xattn {
 namespace {

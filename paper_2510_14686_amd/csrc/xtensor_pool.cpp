@@ -7,7 +7,8 @@
 //   * "Low Overhead Allocation": a finished request's pages stay mapped and are marked Reusable; a new
 //     request whose size matches such a set takes the whole range over (no Map/Unmap); pages for the
 //     next tokens are mapped ahead of time by a background thread.
-// Host code only; the kernels never see any of this (they get a base address and a length).
+// Host code only, no HIP types: the driver calls go through the table of vmm_driver.h.  The kernels
+// never see any of this (they get a base address and a length).
 #include <condition_variable>
 #include <cstdint>
 #include <deque>
@@ -18,134 +19,12 @@
 #include <unordered_set>
 #include <vector>
 
-#include <hip/hip_runtime.h>
-
 #include "../../include/xattn.h"
 #include "vmm_driver.h"
 #include "xattn_internal.h"
 
 namespace xattn {
 namespace {
-
-// ------------------------------------------------------------------------------------ drivers
-int hip_check_device(int device, size_t page_bytes) {
-    int n = 0;
-    hipError_t e = hipGetDeviceCount(&n);
-    if (e != hipSuccess) return fail_hip(e, "hipGetDeviceCount");
-    if (device < 0 || device >= n) return fail(XATTN_EINVAL, "device %d out of range", device);
-    hipMemAllocationProp prop = {};
-    prop.type = hipMemAllocationTypePinned;
-    prop.location.type = hipMemLocationTypeDevice;
-    prop.location.id = device;
-    size_t gran = 0;
-    e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum);
-    if (e != hipSuccess) return fail_hip(e, "hipMemGetAllocationGranularity");
-    if (gran == 0 || page_bytes % gran != 0)
-        return fail(XATTN_EUNSUPPORTED, "mapping granularity %zu does not divide the %zu-byte page", gran, page_bytes);
-    return XATTN_OK;
-}
-int hip_reserve(size_t bytes, size_t align, void** va_out) {
-    hipError_t e = hipMemAddressReserve(va_out, bytes, align, nullptr, 0);
-    return e == hipSuccess ? XATTN_OK : fail_hip(e, "hipMemAddressReserve");
-}
-int hip_free_va(void* va, size_t bytes) {
-    hipError_t e = hipMemAddressFree(va, bytes);
-    return e == hipSuccess ? XATTN_OK : fail_hip(e, "hipMemAddressFree");
-}
-int hip_create(int device, size_t bytes, uint64_t* handle_out) {
-    hipMemAllocationProp prop = {};
-    prop.type = hipMemAllocationTypePinned;
-    prop.location.type = hipMemLocationTypeDevice;
-    prop.location.id = device;
-    hipMemGenericAllocationHandle_t h;
-    hipError_t e = hipMemCreate(&h, bytes, &prop, 0);
-    if (e != hipSuccess) return fail_hip(e, "hipMemCreate");
-    *handle_out = (uint64_t)(uintptr_t)h;
-    return XATTN_OK;
-}
-int hip_release(uint64_t handle) {
-    hipError_t e = hipMemRelease((hipMemGenericAllocationHandle_t)(uintptr_t)handle);
-    return e == hipSuccess ? XATTN_OK : fail_hip(e, "hipMemRelease");
-}
-int hip_map(void* va, size_t bytes, uint64_t handle, int device) {
-    hipError_t e = hipMemMap(va, bytes, 0, (hipMemGenericAllocationHandle_t)(uintptr_t)handle, 0);
-    if (e != hipSuccess) return fail_hip(e, "hipMemMap");
-    hipMemAccessDesc access = {};
-    access.location.type = hipMemLocationTypeDevice;
-    access.location.id = device;
-    access.flags = hipMemAccessFlagsProtReadWrite;
-    e = hipMemSetAccess(va, bytes, &access, 1);
-    if (e != hipSuccess) {
-        (void)hipMemUnmap(va, bytes);
-        return fail_hip(e, "hipMemSetAccess");
-    }
-    return XATTN_OK;
-}
-int hip_unmap(void* va, size_t bytes) {
-    hipError_t e = hipMemUnmap(va, bytes);
-    return e == hipSuccess ? XATTN_OK : fail_hip(e, "hipMemUnmap");
-}
-const VmmDriver kHipDriver = {hip_check_device, hip_reserve, hip_free_va, hip_create, hip_release, hip_map, hip_unmap};
-
-// Host-only stand-in: hands out addresses from a counter, keeps counts, fails on request.
-struct FakeState {
-    std::mutex mu;
-    bool on = false;
-    uint64_t next_va = 0x100000000000ull;
-    uint64_t next_handle = 1;
-    size_t reservations = 0, handles = 0, mappings = 0;
-    int fail_op = -1;        // index into the driver table (1 reserve, 3 create, 5 map, 6 unmap ...)
-    int fail_after = 0;      // that many calls of fail_op succeed first
-} g_fake;
-
-bool fake_should_fail(int op) {
-    if (g_fake.fail_op != op) return false;
-    if (g_fake.fail_after > 0) { --g_fake.fail_after; return false; }
-    g_fake.fail_op = -1;     // fail once
-    return true;
-}
-int fake_check_device(int device, size_t) {
-    return device == 0 ? XATTN_OK : fail(XATTN_EINVAL, "device %d out of range", device);
-}
-int fake_reserve(size_t bytes, size_t align, void** va_out) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    if (fake_should_fail(1)) return fail(XATTN_ENOMEM, "fake driver: reserve refused");
-    g_fake.next_va = (g_fake.next_va + align - 1) / align * align;
-    *va_out = reinterpret_cast<void*>(g_fake.next_va);
-    g_fake.next_va += bytes;
-    ++g_fake.reservations;
-    return XATTN_OK;
-}
-int fake_free_va(void*, size_t) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    --g_fake.reservations;
-    return XATTN_OK;
-}
-int fake_create(int, size_t, uint64_t* handle_out) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    if (fake_should_fail(3)) return fail(XATTN_ENOMEM, "fake driver: create refused");
-    *handle_out = g_fake.next_handle++;
-    ++g_fake.handles;
-    return XATTN_OK;
-}
-int fake_release(uint64_t) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    --g_fake.handles;
-    return XATTN_OK;
-}
-int fake_map(void*, size_t, uint64_t, int) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    if (fake_should_fail(5)) return fail(XATTN_EHIP, "fake driver: map refused");
-    ++g_fake.mappings;
-    return XATTN_OK;
-}
-int fake_unmap(void*, size_t) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    if (fake_should_fail(6)) return fail(XATTN_EHIP, "fake driver: unmap refused");
-    --g_fake.mappings;
-    return XATTN_OK;
-}
-const VmmDriver kFakeDriver = {fake_check_device, fake_reserve, fake_free_va, fake_create, fake_release, fake_map, fake_unmap};
 
 // ------------------------------------------------------------------------------------ pool
 constexpr size_t kPage = XTENSOR_CHUNK_BYTES;
@@ -257,7 +136,7 @@ int grow_locked(Pool* p, PoolRange* r, size_t want_pages) {
 }
 
 void worker_main(Pool* p) {
-    if (!g_fake.on) (void)hipSetDevice(p->device);
+    vmm_driver().bind_thread(p->device);
     std::unique_lock<std::mutex> lock(p->mu);
     for (;;) {
         p->cv_jobs.wait(lock, [&] { return p->stop || !p->jobs.empty(); });
@@ -285,29 +164,11 @@ size_t pages_for(size_t bytes) { return (bytes + kPage - 1) / kPage; }
 
 }  // namespace
 
-const VmmDriver& vmm_driver() { return g_fake.on ? kFakeDriver : kHipDriver; }
-
 }  // namespace xattn
 
 using namespace xattn;
 
 extern "C" {
-
-int xtensor_test_fake_driver(int enable, int fail_op, int fail_after) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    g_fake.on = enable != 0;
-    g_fake.fail_op = fail_op;
-    g_fake.fail_after = fail_after;
-    return XATTN_OK;
-}
-
-int xtensor_test_fake_counts(size_t* reservations, size_t* handles, size_t* mappings) {
-    std::lock_guard<std::mutex> lock(g_fake.mu);
-    if (reservations) *reservations = g_fake.reservations;
-    if (handles) *handles = g_fake.handles;
-    if (mappings) *mappings = g_fake.mappings;
-    return XATTN_OK;
-}
 
 int xtensor_pool_create(int device, size_t n_pages, uint64_t seed, void** pool_out) {
     if (!pool_out) return fail(XATTN_EINVAL, "xtensor_pool_create: pool_out is NULL");

@@ -53,3 +53,39 @@ def test_argument_checks_need_no_gpu():
     with pytest.raises(binding.XattnError) as e:
         binding.xtensor_unmap(0)
     assert e.value.status == binding.XATTN_EINVAL
+
+
+def test_test_hooks_are_not_part_of_the_product_library():
+    from paper_2510_14686_amd import binding
+    lib = binding.load_library()
+    for name in ("xtensor_test_fake_driver", "xtensor_test_fail_next", "xtensor_test_fake_counts", "xattn_test_plan"):
+        assert not hasattr(lib, name), name
+    assert not any("test" in n for n in _declared_functions())
+
+
+def test_workspace_sizes_of_both_operators():
+    """xattn_workspace_bytes / xattn_mla_workspace_bytes (host arithmetic only): the layouts the header
+    states, for the automatic piece count of a device-less process (256) and for a configured one."""
+    from paper_2510_14686_amd import binding
+
+    def up(x):
+        return (x + 255) // 256 * 256
+
+    binding.xattn_configure(binding.XATTN_CFG_PIECES, 0)
+    try:
+        for pieces in (0, 40):
+            binding.xattn_configure(binding.XATTN_CFG_PIECES, pieces)
+            P = pieces or 256
+            B, T, Hq = 64, 2, 32
+            slots, rows = P + B, T * Hq
+            assert binding.xattn_workspace_bytes(B, T, Hq, 8, 128) == up(B * 8) + up(slots * rows * 8) + up(slots * rows * 512)
+            H = 128
+            rows = T * H
+            assert binding.xattn_mla_workspace_bytes(B, T, H, 512, 64) == up(B * 8) + up(slots * rows * 16) + up(slots * rows * 1024)
+    finally:
+        binding.xattn_configure(binding.XATTN_CFG_PIECES, 0)
+    for bad in ((0, 1, 128, 512, 64), (1, 1, 128, 256, 64), (1, 16, 512, 512, 64), (5000, 1, 8, 512, 64)):
+        with pytest.raises(binding.XattnError):
+            binding.xattn_mla_workspace_bytes(*bad)
+    with pytest.raises(binding.XattnError):
+        binding.xattn_workspace_bytes(1, 1, 8, 3, 128)

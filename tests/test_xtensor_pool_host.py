@@ -1,9 +1,11 @@
 """The xTensor page pool's bookkeeping (section 4.3: page triples, on-demand mapping, page reuse,
-asynchronous pre-mapping, lazy release) and its failure handling, on the host-only stand-in driver.
-No GPU and no device memory is involved; the GPU tests run the same pool on the HIP driver."""
+asynchronous pre-mapping, lazy release) and its failure handling, in the host test library: the pool's
+source built against a host-only stand-in for the virtual-memory driver.  No GPU and no device memory
+is involved; the GPU tests run the same pool source, in libxattn.so, on the HIP driver."""
 import numpy as np
 import pytest
 
+import host_lib
 import oracle
 import paper_2510_14686_amd as xa
 from paper_2510_14686_amd import binding as B
@@ -14,18 +16,19 @@ FREE, ALLOCATED, MAPPED, REUSABLE = 0, 1, 2, 3
 
 @pytest.fixture(autouse=True)
 def fake_driver():
-    xa.xtensor_test_fake_driver(True)
-    base = xa.xtensor_test_fake_counts()
-    yield
-    # every test must leave the stand-in as it found it: nothing reserved, created or mapped is leaked
-    assert xa.xtensor_test_fake_counts() == base
-    xa.xtensor_test_fake_driver(False)
+    with host_lib.as_product_library():
+        host_lib.fail_next(-1)
+        base = host_lib.fake_counts()
+        yield
+        # every test must leave the stand-in as it found it: nothing reserved, created or mapped is leaked
+        assert host_lib.fake_counts() == base
+        host_lib.fail_next(-1)
 
 
 def test_pool_starts_with_free_pages_and_ends_clean():
     pool = xa.xtensor_pool_create(0, 16, 1)
     assert xa.xtensor_pool_counts(pool) == (16, 0, 0, 0)
-    assert xa.xtensor_test_fake_counts()[1] == 16           # all physical pages exist up front
+    assert host_lib.fake_counts()[1] == 16           # all physical pages exist up front
     for i in range(16):
         assert xa.xtensor_page_info(pool, i) == (FREE, 0)
     xa.xtensor_pool_destroy(pool)
@@ -88,16 +91,16 @@ def test_finished_request_leaves_a_reusable_set_that_a_matching_request_takes_ov
         assert xa.xtensor_page_info(pool, int(i))[0] == REUSABLE
     with pytest.raises(xa.XattnError):
         xa.xtensor_grow(rng, 6 * PAGE)                        # the old request's handle is closed
-    maps_before = xa.xtensor_test_fake_counts()[2]
+    maps_before = host_lib.fake_counts()[2]
     # a request of another size does not match: fresh range, fresh pages
     b2, r2, reused2 = xa.xtensor_open(pool, 11, 8 * PAGE, 4 * PAGE)
     assert not reused2 and b2 != base
     # a request of the same size takes the set over: same addresses, same pages, no map call
-    maps_mid = xa.xtensor_test_fake_counts()[2]
+    maps_mid = host_lib.fake_counts()[2]
     b3, r3, reused3 = xa.xtensor_open(pool, 12, 8 * PAGE, 5 * PAGE - 100)
     assert reused3 and b3 == base
     assert np.array_equal(xa.xtensor_range_pages(r3), pages)
-    assert xa.xtensor_test_fake_counts()[2] == maps_mid == maps_before + 4
+    assert host_lib.fake_counts()[2] == maps_mid == maps_before + 4
     for i in pages:
         assert xa.xtensor_page_info(pool, int(i)) == (MAPPED, 12)
     assert xa.xtensor_pool_counts(pool) == (7, 0, 9, 0)
@@ -139,11 +142,11 @@ def test_reusable_sets_are_released_lazily_when_the_pool_runs_dry():
 @pytest.mark.parametrize("fail_op,fail_after", [(5, 0), (5, 2), (1, 0)])
 def test_failed_open_rolls_everything_back(fail_op, fail_after):
     pool = xa.xtensor_pool_create(0, 8, 7)
-    xa.xtensor_test_fake_driver(True, fail_op, fail_after)    # map (5) or reserve (1) fails once
+    host_lib.fail_next(fail_op, fail_after)    # map (5) or reserve (1) fails once
     with pytest.raises(xa.XattnError):
         xa.xtensor_open(pool, 1, 8 * PAGE, 4 * PAGE)
     assert xa.xtensor_pool_counts(pool) == (8, 0, 0, 0)       # no page stuck in Allocated or Mapped
-    res, handles, maps = xa.xtensor_test_fake_counts()
+    res, handles, maps = host_lib.fake_counts()
     assert maps == 0 and handles == 8
     _, r, _ = xa.xtensor_open(pool, 1, 8 * PAGE, 4 * PAGE)    # and the pool still works
     xa.xtensor_close(r, False)
@@ -153,7 +156,7 @@ def test_failed_open_rolls_everything_back(fail_op, fail_after):
 def test_failed_grow_keeps_what_the_range_had():
     pool = xa.xtensor_pool_create(0, 8, 8)
     _, r, _ = xa.xtensor_open(pool, 1, 8 * PAGE, 2 * PAGE)
-    xa.xtensor_test_fake_driver(True, 5, 1)                   # second map of the grow fails
+    host_lib.fail_next(5, 1)                   # second map of the grow fails
     with pytest.raises(xa.XattnError):
         xa.xtensor_grow(r, 6 * PAGE)
     assert len(xa.xtensor_range_pages(r)) == 3                # two it had, one it got before the failure
@@ -164,11 +167,11 @@ def test_failed_grow_keeps_what_the_range_had():
 
 
 def test_pool_creation_failure_releases_the_pages_already_created():
-    xa.xtensor_test_fake_driver(True, 3, 5)                   # sixth page creation fails
+    host_lib.fail_next(3, 5)                   # sixth page creation fails
     with pytest.raises(xa.XattnError) as e:
         xa.xtensor_pool_create(0, 16, 9)
     assert e.value.status == B.XATTN_ENOMEM
-    assert xa.xtensor_test_fake_counts()[1] == 0
+    assert host_lib.fake_counts()[1] == 0
 
 
 def test_asynchronous_premapping():
