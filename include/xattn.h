@@ -106,8 +106,9 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
  * out     DEVICE bf16 [batch, q_len, n_heads, d_latent];  lse DEVICE fp32 [batch, q_len, n_heads] or NULL
  * Supported: d_latent = 512, d_rope = 64, q_len * n_heads <= 4096, batch <= 4096; otherwise
  * XATTN_EUNSUPPORTED.  Same partition, workspace, stream, capture and ownership rules as xattn_decode.
- * Numerics: fp32 accumulation; the softmax weights enter the value product as bf16 (see
- * XATTN_CFG_PV_MODE); the partial output rows of a sequence that is split over several compute units
+ * Numerics: fp32 accumulation; the softmax weights enter the value product as bf16, with 16
+ * significant bits where a key dominates its row and 8 elsewhere (see XATTN_CFG_PV_MODE), and the
+ * output is divided by the sum of the weights as they entered; the partial output rows of a sequence that is split over several compute units
  * pass through the workspace as fp16 scaled by the row's largest magnitude (11 significant bits per
  * element).  q and the cached rows must be finite: an infinity or NaN makes the rows it reaches
  * unspecified.
@@ -150,8 +151,10 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *                               MFMA on hi + lo bf16 parts of the weights (16 significant bits);
  *                               1 = fp32 MFMA (weights exact, slower); 2 = one bf16 MFMA (weights
  *                               rounded to bf16)
- *                               (xattn_mla_decode: 0 and 2 = one bf16 MFMA, output normalised by the
- *                               sum of the rounded weights; 1 = hi + lo parts, normalised by the exact sum)
+ *                               (xattn_mla_decode: 0 = default, hi + lo bf16 parts for the first 128 keys
+ *                               of every segment and wherever a key carries 1/8 or more of its row's
+ *                               running sum, one bf16 elsewhere; 1 = hi + lo parts everywhere;
+ *                               2 = one bf16 per weight everywhere, less exact on peaked rows)
  *   XATTN_CFG_MLA_LAYOUT        xattn_mla_decode workgroup shape for more than 64 query rows per sequence:
  *                               0 = automatic (8 waves of one 16-row tile), 1 = 4 waves of one tile,
  *                               2 = 4 waves of two tiles; for experiments, results do not depend on it

@@ -368,7 +368,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;
     prm.layout = g_cfg_mla_layout;
-    prm.hi_lo = g_cfg_pv_mode == 1 ? 1 : 0;       // XATTN_CFG_PV_MODE 1: weights as hi + lo bf16 parts
+    prm.weight_mode = g_cfg_pv_mode;
     hipEvent_t* events = nullptr;
     st = timing_events(&events);
     if (st != XATTN_OK) return st;

@@ -64,7 +64,8 @@ struct MlaParams {
     int32_t* meta;                   // int32 [batch, 2]
     int n_pieces, min_piece_tokens;
     int layout;                      // 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave
-    int hi_lo;                       // softmax weights into the value product as hi + lo bf16 parts
+    int weight_mode;                 // softmax weights in the value product: 0 default (hi + lo bf16 parts where a key
+                                     // dominates, one bf16 elsewhere), 1 hi + lo everywhere, 2 one bf16 everywhere
 };
 void mla_block_shape(int rows_total, int layout, int* waves, int* tiles_per_wave);
 // Enqueues the decode kernel and its merge kernel; events as for launch_decode.

@@ -29,14 +29,21 @@
 //     reference maximum of a row moves only when a block exceeds it by more than 2^8, so the 128
 //     accumulators are rescaled about once per segment instead of in most blocks;
 //   * O^T += C[:, 0:512]^T P^T: bf16 MFMA 16x16x32 over the 32 keys, the A operand (16 value columns x
-//     8 keys per lane) fetched with LDS transposing reads.  P goes in as one bf16 per weight and the
-//     output is normalised by the sum of those rounded weights; on request as hi + lo bf16 parts
-//     (two MFMAs, weights to 16 bits, normalised by the exact sum).
+//     8 keys per lane) fetched with LDS transposing reads.  A weight enters the product as one bf16
+//     where it is small against the row's sum, and as hi + lo bf16 parts (two MFMAs, 16 significant
+//     bits) where it is not: in the first kExactBlocks blocks of every segment, whose keys' share of
+//     the final sum is not yet known, and in any later block that holds a key with at least 1/8 of
+//     the row's running sum.  The output is normalised by the sum of the weights as they entered
+//     the product.  (Rounding every weight to one bf16 costs nothing on diffuse rows, where the
+//     errors average out; where a few keys carry the row, outputs are large enough for bf16 output
+//     rounding to use up most of the tolerance, and the weights' own 2^-9 no longer fits beside it.)
 // LDS reads are issued a few steps ahead of the MFMAs that use them, pinned with scheduling groups.
 // A segment that is not a whole sequence leaves its rows in the workspace as fp16, scaled by the
 // row's largest magnitude, with (m, l, lq, 1 / scale) in fp32; the merge kernel combines them.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "xattn_device.h"
 #include "xattn_kernels.h"
@@ -76,6 +83,12 @@ constexpr int kLdsOutPerWave = 16 * kOutPitch;
 // the block loop (2.3 us per 32 tokens).
 constexpr int kMlaSegCost = 192;
 constexpr float kLazyLog2 = 8.0f;                // slack of the softmax reference maximum, in powers of two
+// Precision of the softmax weights in the value product (see the header comment).
+constexpr int kLoNever = 0;                      // one bf16 per weight everywhere
+constexpr int kLoAlways = 1;                     // hi + lo bf16 parts everywhere
+constexpr int kLoDynamic = 2;                    // hi + lo parts only in blocks with a dominant key
+constexpr int kExactBlocks = 4;                  // default mode: the first blocks of a segment run as kLoAlways
+constexpr float kDominantShare = 8.0f;           // a key is dominant from 1 / 8 of the row's running sum
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
@@ -83,16 +96,20 @@ typedef short s16x4v_t __attribute__((ext_vector_type(4)));
 // Running state of one 16-row tile.  Lane (kb, n) holds row n.
 struct MlaTile {
     f32x4_t o[kColTiles];      // o[ct][i]: column 16 ct + 4 kb + i
-    float m, l;                // running maximum (log2 domain) and this lane's share of the sum
-    float lq;                  // the same sum over the weights as they enter the value product
+    float m, l;                // reference maximum (log2 domain) and the running sum over all keys of the row
+    float lq;                  // this lane's share of the sum over the weights as they entered the value product
 };
 
 // The loads are written as assembly so that the compiler does not order them against LDS reads: it
 // cannot tell the two halves of the double buffer apart and would wait for every outstanding load
 // before each read.  dma_wait() before the workgroup barrier is what makes a block visible.
 __device__ __forceinline__ void dma16(u32x4_t rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 1\n\tbuffer_load_dwordx4 %1, %2, %3 offen nt lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+    // m0 carries the LDS address of the load.  The compiler keeps values of its own in m0 (lane
+    // indices, LDS-DMA bases) and does not accept m0 in a clobber list, so the statement saves and
+    // restores it; the load has read m0 by the time it is issued.
+    uint32_t saved_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 1\n\tbuffer_load_dwordx4 %2, %3, %4 offen nt lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(saved_m0) : "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
 }
 // Waits until at most n of this wave's loads are outstanding (they complete in order): n = the number
 // of loads of the newest block leaves the block before it complete.
@@ -205,12 +222,12 @@ struct QkSched {
 };
 
 // One 32-key block from LDS against this wave's RT tiles of 16 rows.  Every operand read from LDS is
-// used for all RT tiles.  kHiLo: the softmax weights go into the value product as hi + lo bf16 parts
-// (two MFMAs, 16 significant bits) instead of one rounded bf16.
+// used for all RT tiles.  kLo: how the softmax weights go into the value product (kLoNever, kLoAlways,
+// kLoDynamic).
 //   qk_base = block + n * kPitch + kb * 16                     (key row n of a tile, chunk kb)
 //   qt_base = block + kTailOff + n * kTailPitch + kb * 16      (the same for the rope part)
 //   pv_base = block + (4 kb + n / 4) * kPitch + (n % 4) * 8    (transposing read, see below)
-template <int RT, bool kHiLo>
+template <int RT, int kLo>
 __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base, const char* qt_base, const char* pv_base,
                                           const bf16x8_t (&qop)[RT][kQRegSteps], const char* q_lds, float scale_log2,
                                           int j_block, const int (&lim)[RT], int kb) {
@@ -271,6 +288,7 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     // Softmax.  The lane's 8 weights of a row, ordered (kt, i), are the B operand of the value product
     // when contraction index 8 kb + 4 kt + i stands for key 16 kt + 4 kb + i.
     bf16x8_t ph[RT], pl[RT];
+    bool with_lo[RT];                // the tile's weights go in as hi + lo parts in this block
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         // Keys at or past lim[rt] (the end of the segment, or the causal limit of the row) count as
@@ -301,14 +319,19 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
             p[t] = fast_exp2(__builtin_fmaf(p[t], scale_log2, -m_use));
             sum += p[t];
         }
-        st[rt].l = st[rt].l * alpha + sum;
+        st[rt].l = st[rt].l * alpha + kb_sum(sum);
         st[rt].m = m_new;
         if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
             for (int ct = 0; ct < kColTiles; ++ct) st[rt].o[ct] *= alpha;
         }
-        // With one bf16 per weight the output is normalised by the sum of the ROUNDED weights: a
-        // softmax over slightly perturbed scores (relative weight error 2^-9, the same for equal
+        // Dominant key: the block's largest weight of a row against the row's sum so far (this block
+        // included), which is at most the sum the output is divided by in the end.  The tile adds the
+        // lo parts if any of its rows has one.
+        with_lo[rt] = kLo == kLoAlways ||
+                      (kLo == kLoDynamic && __builtin_amdgcn_ballot_w64(fast_exp2(mx - m_use) * kDominantShare >= st[rt].l) != 0);
+        // Where a weight goes in as one bf16 the output is normalised by the sum of the ROUNDED weights:
+        // a softmax over slightly perturbed scores (relative weight error 2^-9, the same for equal
         // weights, none for a lone key) instead of rounded weights over an exact sum.
         uint32_t h[4], lo[4] = {0u, 0u, 0u, 0u};
         float sum_q = 0.0f;
@@ -318,10 +341,18 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
             const bf16x2_t hh = __builtin_convertvector(pp, bf16x2_t);
             const f32x2_t back = __builtin_convertvector(hh, f32x2_t);
             h[u] = __builtin_bit_cast(uint32_t, hh);
-            if (kHiLo) lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp - back, bf16x2_t));
-            else sum_q += back[0] + back[1];
+            sum_q += back[0] + back[1];
+            p[2 * u] -= back[0];
+            p[2 * u + 1] -= back[1];
         }
-        st[rt].lq = kHiLo ? st[rt].l : st[rt].lq * alpha + sum_q;
+        if (with_lo[rt]) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const f32x2_t rest = {p[2 * u], p[2 * u + 1]};
+                lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
+            }
+        }
+        st[rt].lq = st[rt].lq * alpha + (with_lo[rt] ? sum : sum_q);
         ph[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{h[0], h[1], h[2], h[3]});
         pl[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
     }
@@ -338,7 +369,7 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt)
                 st[rt].o[c2 + u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[c2 + u], ph[rt], st[rt].o[c2 + u], 0, 0, 0);
-        if (kHiLo) {
+        if (kLo == kLoAlways) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -348,14 +379,24 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     }
 #pragma unroll
     for (int c2 = 0; c2 < kColTiles; c2 += 2) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2 * RT * (kHiLo ? 2 : 1), 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * RT * (kLo == kLoAlways ? 2 : 1), 0);
         if (c2 + 2 * kVAhead < kColTiles) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+    }
+    if (kLo == kLoDynamic) {
+        // The rare block with a dominant key: a second pass over the value fragments with the lo parts.
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            if (!with_lo[rt]) continue;
+#pragma unroll
+            for (int ct = 0; ct < kColTiles; ++ct)      // fully unrolled: the accumulators are registers
+                st[rt].o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(load_v(ct), pl[rt], st[rt].o[ct], 0, 0, 0);
+        }
     }
 }
 
-// grid.x = pieces (rounded up to a multiple of 8) x groups of 16 * RT * NW rows; block = 64 * NW.  Wave w owns row tiles
-// w * RT .. w * RT + RT - 1 of its group.
-template <int NW, int RT, bool kHiLo>
+// kMode: 0 = default (hi + lo weights in the first kExactBlocks blocks of a segment and wherever a key
+// dominates its row), 1 = hi + lo weights everywhere, 2 = one bf16 per weight everywhere.
+template <int NW, int RT, int kMode>
 __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     __shared__ __attribute__((aligned(16))) char lds_c[kStages * kLdsBlock];
     // Per wave and tile: the Q chunks of steps kQRegSteps.. (each lane reads back what it wrote); the
@@ -457,27 +498,34 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         const int n_blocks = (j1 - j0 + kMlaKeys - 1) / kMlaKeys;
         if (n_blocks > 1) block_to_lds<NW>(lds_c + kLdsBlock, rc, j0 + kMlaKeys, wave, dma);   // block 1 -> buffer 1
         int cur_buf = 0, next_buf = 2;         // block blk sits in buffer blk % 3, block blk + 2 goes to next_buf
-        for (int blk = 0; blk < n_blocks; ++blk) {
+        // One block: every wave waits for its own loads of block blk (those of block blk + 1 may stay
+        // in flight), then the barrier: block blk is in LDS and everyone is done reading block
+        // blk - 1, whose buffer the loads of block blk + 2 may overwrite.
+        auto step = [&](int blk, auto lo_mode) {
             const char* cur = lds_c + cur_buf * kLdsBlock;
-            // Every wave waits for its own loads of block blk (those of block blk + 1 may stay in
-            // flight), then the barrier: block blk is in LDS and everyone is done reading block
-            // blk - 1, whose buffer the loads of block blk + 2 may overwrite.
             dma_wait(blk + 1 < n_blocks ? my_loads : 0);
             __syncthreads();
             if (blk + 2 < n_blocks)
                 block_to_lds<NW>(lds_c + next_buf * kLdsBlock, rc, j0 + (blk + 2) * kMlaKeys, wave, dma);
-            mla_block<RT, kHiLo>(st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb);
+            mla_block<RT, decltype(lo_mode)::value>(st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2,
+                                                    j0 + blk * kMlaKeys, lim, kb);
             cur_buf = cur_buf == kStages - 1 ? 0 : cur_buf + 1;
             next_buf = next_buf == kStages - 1 ? 0 : next_buf + 1;
-        }
+        };
+        // Default mode: the first blocks of a segment with hi + lo weights, the others with hi + lo
+        // only where a key dominates.
+        const int n_exact = kMode == 1 ? n_blocks : kMode == 2 ? 0 : (n_blocks < kExactBlocks ? n_blocks : kExactBlocks);
+        int blk = 0;
+        for (; blk < n_exact; ++blk) step(blk, std::integral_constant<int, kLoAlways>());
+        for (; blk < n_blocks; ++blk) step(blk, std::integral_constant<int, kMode == 0 ? kLoDynamic : kLoNever>());
         __syncthreads();          // the next segment's first block reuses buffer 0
 
         // Store, 64 columns at a time through this wave's LDS so that a store instruction writes whole
         // 256-byte pieces of rows.
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
-            const float l = kb_sum(st[rt].l);
-            const float lq = kHiLo ? l : kb_sum(st[rt].lq);
+            const float l = st[rt].l;
+            const float lq = kb_sum(st[rt].lq);
             // A partial row goes out as fp16 after scaling its largest magnitude to 2^15 (the scale's
             // inverse is kept in fp32 beside the row's m and l): half the bytes of fp32 to write here
             // and to read back in the merge.  Every element keeps 11 significant bits of its own
@@ -601,8 +649,9 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
 
 template <int NW, int RT>
 hipError_t launch_mla_cfg(const MlaParams& prm, dim3 grid, hipStream_t stream) {
-    if (prm.hi_lo) hipLaunchKernelGGL((mla_decode_kernel<NW, RT, true>), grid, dim3(64 * NW), 0, stream, prm);
-    else hipLaunchKernelGGL((mla_decode_kernel<NW, RT, false>), grid, dim3(64 * NW), 0, stream, prm);
+    if (prm.weight_mode == 1) hipLaunchKernelGGL((mla_decode_kernel<NW, RT, 1>), grid, dim3(64 * NW), 0, stream, prm);
+    else if (prm.weight_mode == 2) hipLaunchKernelGGL((mla_decode_kernel<NW, RT, 2>), grid, dim3(64 * NW), 0, stream, prm);
+    else hipLaunchKernelGGL((mla_decode_kernel<NW, RT, 0>), grid, dim3(64 * NW), 0, stream, prm);
     return hipGetLastError();
 }
 

@@ -126,6 +126,56 @@ def test_capture_refuses_to_grow_the_workspace():
         assert float(marker[0]) == 1.0                             # the capture recorded the rest and replays
 
 
+def test_recorded_graph_stays_valid_after_the_workspace_has_grown():
+    """A graph records the address of its stream's workspace.  A later, larger eager call on the same
+    stream has to replace that workspace; the buffer the graph uses is retired, not freed, so replaying
+    the older graph still writes and reads live memory (compared with the oracle after other work has
+    had the chance to reuse freed memory)."""
+    import torch
+
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
+    B, T, Hq, Hkv = 4, 1, 8, 2
+    lens = np.array([3000, 2000, 50, 4000], np.int32)          # split over many workgroups: partial results in the workspace
+    q = normal_bf16(97, 0, B * T * Hq * D).reshape(B, T, Hq, D)
+    ks = [normal_bf16(97, 1 + 2 * b, int(L) * Hkv * D).reshape(int(L), Hkv, D) for b, L in enumerate(lens)]
+    vs = [normal_bf16(97, 2 + 2 * b, int(L) * Hkv * D).reshape(int(L), Hkv, D) for b, L in enumerate(lens)]
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, SCALE)
+    side = torch.cuda.Stream()                                  # a fresh stream: its workspace starts empty
+    with xa.KVStore(ks, vs) as store:
+        qd = torch.from_numpy(q.view(np.int16)).cuda()
+        lens_d = torch.from_numpy(lens).cuda()
+        out = torch.zeros((B, T, Hq, D), dtype=torch.int16, device="cuda")
+        lse = torch.zeros((B, T, Hq), dtype=torch.float32, device="cuda")
+        xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, lse, side)
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            xa.xattn_decode(qd, store.k_ptrs, store.v_ptrs, lens_d, B, T, Hq, Hkv, D, SCALE, out, lse, side)
+        # a larger shape on the same stream: 16 times the query rows, the workspace must be replaced
+        T2, Hq2, Hkv2 = 4, 32, 8
+        ks2 = [normal_bf16(98, 1 + b, 2000 * Hkv2 * D).reshape(2000, Hkv2, D) for b in range(B)]
+        with xa.KVStore(ks2, ks2) as store2:
+            q2 = torch.zeros((B, T2, Hq2, D), dtype=torch.int16, device="cuda")
+            lens2 = torch.full((B,), 2000, dtype=torch.int32, device="cuda")
+            out2 = torch.zeros((B, T2, Hq2, D), dtype=torch.int16, device="cuda")
+            assert xa.xattn_workspace_bytes(B, T2, Hq2, Hkv2, D) > 2 * xa.xattn_workspace_bytes(B, T, Hq, Hkv, D)
+            xa.xattn_decode(q2, store2.k_ptrs, store2.v_ptrs, lens2, B, T2, Hq2, Hkv2, D, SCALE, out2, None, side)
+            side.synchronize()
+        # allocations that would land in memory the library had freed
+        junk = [torch.full((1 << 20,), 0x7FC07FC0, dtype=torch.int32, device="cuda") for _ in range(8)]
+        torch.cuda.synchronize()
+        for r in range(2):
+            out.fill_(0x7FC0)
+            lse.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert_parity(out.cpu().numpy().view(np.uint16), lse.cpu().numpy(), ref_out, ref_lse, "replay %d after growth" % r)
+        del junk
+
+
 def test_graph_replay_of_latent_kv_decode():
     """xattn_mla_decode recorded once and replayed with other lengths and data: every replay against
     the oracle and bit-identical to an eager call (eager work and synchronisations in between)."""

@@ -55,21 +55,29 @@ def test_maximum_query_tokens_and_rows(T, Hq, Hkv):
 
 @pytest.mark.parametrize("B,T,H,lens", [(2, 16, 256, [16, 777]), (3, 1, 4096, [1, 40, 300]), (4096, 1, 16, None)])
 def test_latent_kv_maximum_rows_and_batch(B, T, H, lens):
-    from gpu_util import assert_parity
+    from gpu_util import TOL_MAX_ABS, assert_parity
     from test_gpu_mla import gpu_mla
     _defaults()
     DQK, DV = 576, 512
-    if lens is None:
+    many_short = lens is None
+    if many_short:
         lens = (1 + (uniform_u64(72, 0, B) % np.uint64(12))).astype(np.int32)
         lens[[7, 4000]] = [500, 65]
     lens = np.asarray(lens, np.int32)
     q = f32_to_bf16(bf16_to_f32(normal_bf16(72, 1, B * T * H * DQK)) * np.float32(math.sqrt(192.0 / DQK))).reshape(B, T, H, DQK)
-    # halved (exact in bf16): with thousands of very short sequences some outputs would otherwise reach
-    # |x| >= 4, where rounding the output to bf16 alone moves it by up to 1.6e-2, past the 1e-2 bar
-    rows = f32_to_bf16(bf16_to_f32(normal_bf16(72, 2, int(lens.sum()) * DQK)) * np.float32(0.5)).reshape(-1, DQK)
+    rows = normal_bf16(72, 2, int(lens.sum()) * DQK).reshape(-1, DQK)
     off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
-    cs = [rows[off[b]:off[b + 1]] for b in range(B)]
     scale = float(np.float32(1.0 / math.sqrt(192.0)))
+    if many_short:
+        # Thousands of one- and two-key sequences of N(0,1) values: some exact outputs reach |x| >= 4,
+        # where rounding the exact result to bf16 alone exceeds the max-abs bar, whatever the kernel
+        # does.  The oracle itself shows it (asserted, so the narrowing below justifies itself); the
+        # cache values of this case are therefore halved, which is exact in bf16.
+        ref_full, _ = oracle.mla(q, [rows[off[b]:off[b + 1]] for b in range(B)], lens, DV, scale)
+        rounding_alone = np.max(np.abs(bf16_to_f32(f32_to_bf16(ref_full.astype(np.float32))).astype(np.float64) - ref_full))
+        assert rounding_alone > TOL_MAX_ABS, "bf16 rounding of the exact result no longer exceeds the bar: drop the halving"
+        rows = f32_to_bf16(bf16_to_f32(rows) * np.float32(0.5))
+    cs = [rows[off[b]:off[b + 1]] for b in range(B)]
     out_bits, lse = gpu_mla(q, cs, lens, scale)
     ref_out, ref_lse = oracle.mla(q, cs, lens, DV, scale)
     assert_parity(out_bits, lse, ref_out, ref_lse, "latent-KV B=%d T=%d H=%d" % (B, T, H))
