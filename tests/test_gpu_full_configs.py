@@ -1,21 +1,17 @@
-"""The four large workloads at full size, in the launch configuration bench.py times (automatic
-partition, xTensor placement where the workload says so), against the fp64 oracle.
-
-Every output row of a sample of sequences is compared element by element (the sample always holds
-the longest and the shortest sequence); the remaining rows are checked for properties that hold at
-any size: finite, and |out| bounded by the largest |V| entry (a convex combination of V rows)."""
+"""The four large workloads and the two latent-KV workloads at full size, in the launch configuration
+bench.py times (automatic partition, xTensor placement where the workload says so), against the fp64
+oracle: every output row of EVERY sequence is compared element by element."""
 import numpy as np
 import pytest
 
 import oracle
-from workloads import CONFIGS, bf16_to_f32
+from workloads import CONFIGS
 
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,n_check", [("qwen3_8b_decode", 64), ("long_context", 6), ("spec_verify", 24),
-                                          ("skewed_xtensor", 64)])
-def test_full_size_workload(name, n_check):
+@pytest.mark.parametrize("name", ["qwen3_8b_decode", "long_context", "spec_verify", "skewed_xtensor"])
+def test_full_size_workload(name):
     import paper_2510_14686_amd as xa
     from gpu_util import assert_parity, gpu_attn
     xa.xattn_configure(xa.XATTN_CFG_PIECES, 0)
@@ -26,22 +22,15 @@ def test_full_size_workload(name, n_check):
     ks, vs = w.make_kv(lens)
     print("case", name, "tokens", int(lens.sum()), flush=True)
     out_bits, lse = gpu_attn(q, ks, vs, lens, w.scale, xtensor=w.xtensor, seed=w.seed)
-    B = w.batch
-    sel = sorted(set(np.linspace(0, B - 1, min(n_check, B)).astype(int).tolist()
-                     + [int(np.argmax(lens)), int(np.argmin(lens))]))
-    ref_out, ref_lse = oracle.attn(q[sel], [ks[b] for b in sel], [vs[b] for b in sel], lens[sel], w.scale)
-    print(name, "max_abs=%.2e rel_l2_rows=%.2e rel_l2=%.2e lse=%.2e"
-          % assert_parity(out_bits[sel], lse[sel], ref_out, ref_lse, name), flush=True)
-    got = bf16_to_f32(out_bits)
-    assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
-    vmax = max(float(np.max(np.abs(bf16_to_f32(v)))) for v in vs)
-    assert float(np.max(np.abs(got))) <= vmax * (1 + 2 ** -7)
+    ref_out, ref_lse = oracle.attn(q, ks, vs, lens, w.scale)
+    print(name, "all %d sequences: max_abs=%.2e rel_l2_rows=%.2e rel_l2=%.2e lse=%.2e"
+          % ((w.batch,) + assert_parity(out_bits, lse, ref_out, ref_lse, name)), flush=True)
 
 
-@pytest.mark.parametrize("name,n_check", [("mla_decode", 6), ("mla_verify", 4)])
-def test_full_size_latent_kv_workload(name, n_check):
+@pytest.mark.parametrize("name", ["mla_decode", "mla_verify"])
+def test_full_size_latent_kv_workload(name):
     """The two latent-KV workloads at full size, as bench.py launches them (automatic partition and
-    workgroup shape, xTensor ranges): sampled sequences element by element, every row bounded."""
+    workgroup shape, xTensor ranges): every sequence element by element."""
     import paper_2510_14686_amd as xa
     from gpu_util import assert_parity
     from test_gpu_mla import gpu_mla
@@ -53,12 +42,6 @@ def test_full_size_latent_kv_workload(name, n_check):
     q, cs = w.make_q(), w.make_cache(lens)
     print("case", name, "tokens", int(lens.sum()), flush=True)
     out_bits, lse = gpu_mla(q, cs, lens, w.scale, xtensor=w.xtensor, seed=w.seed)
-    B = w.batch
-    sel = sorted(set(np.linspace(0, B - 1, n_check).astype(int).tolist() + [int(np.argmax(lens)), int(np.argmin(lens))]))
-    ref_out, ref_lse = oracle.mla(q[sel], [cs[b] for b in sel], lens[sel], w.d_latent, w.scale)
-    print(name, "max_abs=%.2e rel_l2_rows=%.2e rel_l2=%.2e lse=%.2e"
-          % assert_parity(out_bits[sel], lse[sel], ref_out, ref_lse, name), flush=True)
-    got = bf16_to_f32(out_bits)
-    assert np.all(np.isfinite(got)) and np.all(np.isfinite(lse))
-    vmax = max(float(np.max(np.abs(bf16_to_f32(c[:, :w.d_latent])))) for c in cs)
-    assert float(np.max(np.abs(got))) <= vmax * (1 + 2 ** -6)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, w.d_latent, w.scale)
+    print(name, "all %d sequences: max_abs=%.2e rel_l2_rows=%.2e rel_l2=%.2e lse=%.2e"
+          % ((w.batch,) + assert_parity(out_bits, lse, ref_out, ref_lse, name)), flush=True)
