@@ -91,6 +91,26 @@ int xattn_decode(const void* q, const void* const* k_ptrs, const void* const* v_
                  int head_dim, float scale, void* out, float* lse, void* stream);
 
 /*
+ * xattn_decode for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels, partition and results
+ * (bit for bit) as xattn_decode; the partial results of split sequences go to a device array of
+ * XATTN_NOALLOC_SCRATCH_BYTES that is part of the library's code object (every GPU the library runs
+ * on holds its copy until the process ends) instead of a workspace from hipMalloc.  The call
+ * allocates nothing: no hipMalloc, hipFree or event creation; xattn_set_workspace and
+ * XATTN_CFG_TIMING do not apply to it.
+ * A shape whose partial results need more than the array holds (see xattn_workspace_bytes; all five
+ * benchmark configurations fit) returns XATTN_EUNSUPPORTED and enqueues nothing.  All calls on a GPU
+ * share that GPU's array, whatever their stream: calls that overlap in time on one GPU race; calls
+ * on one stream are ordered by it.  Nothing in the array has to start at zero (every word that is
+ * read was written by the same call before).  The array's address is resolved on the first call on a
+ * device; make that first call outside graph capture.
+ */
+#define XATTN_NOALLOC_SCRATCH_BYTES ((size_t)32 << 20)
+int xattn_decode_noalloc(const void* q, const void* const* k_ptrs, const void* const* v_ptrs,
+                         const int32_t* kv_lens, int batch, int q_len, int n_q_heads, int n_kv_heads,
+                         int head_dim, float scale, void* out, float* lse, void* stream);
+
+/*
  * Latent-KV decode attention, the MLA-shaped operator the paper itself adapts (section 4.3
  * "Operator Adaptation"; section 4.4.1 "MLA Optimization": with m speculated tokens, m+1 query
  * tokens per sequence, all heads, are multiplied with the same cached rows).  Per token the cache

@@ -18,7 +18,7 @@ XATTN_OK, XATTN_EINVAL, XATTN_EUNSUPPORTED, XATTN_ENOMEM, XATTN_EHIP = 0, -1, -2
 XATTN_CFG_PIECES, XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_TIMING, XATTN_CFG_PATH, XATTN_CFG_PV_MODE, XATTN_CFG_MLA_LAYOUT = 0, 1, 2, 3, 4, 5
 XTENSOR_CHUNK_BYTES = 2 << 20
 
-EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_workspace_bytes", "xattn_set_workspace",
+EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_decode_noalloc", "xattn_workspace_bytes", "xattn_set_workspace",
            "xattn_configure", "xattn_timing_read", "xtensor_map", "xtensor_unmap", "xtensor_chunk_order",
            "xtensor_physical_view", "xtensor_upload", "xtensor_download",
            "xtensor_pool_create", "xtensor_pool_destroy", "xtensor_pool_counts", "xtensor_page_info",
@@ -43,6 +43,7 @@ def _signatures():
     return {
         "xattn_last_error": (ctypes.c_char_p, []),
         "xattn_decode": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp]),
+        "xattn_decode_noalloc": (i32, [vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp]),
         "xattn_workspace_bytes": (sz, [i32] * 5),
         "xattn_mla_workspace_bytes": (sz, [i32] * 5),
         "xattn_set_workspace": (i32, [vp, sz]),
@@ -129,6 +130,19 @@ def xattn_decode(q, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_q_heads: 
     _check(load_library().xattn_decode(_ptr(q), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(kv_lens), batch, q_len,
                                        n_q_heads, n_kv_heads, head_dim, ctypes.c_float(scale), _ptr(out),
                                        _ptr(lse), stream))
+
+
+def xattn_decode_noalloc(q, k_ptrs, v_ptrs, kv_lens, batch: int, q_len: int, n_q_heads: int, n_kv_heads: int,
+                         head_dim: int, scale: float, out, lse=None, stream=None) -> None:
+    """xattn_decode without any device allocation (fixed scratch array); see include/xattn.h."""
+    if stream is not None and not isinstance(stream, int):
+        stream = int(stream.cuda_stream)
+    _check(load_library().xattn_decode_noalloc(_ptr(q), _ptr(k_ptrs), _ptr(v_ptrs), _ptr(kv_lens), batch, q_len,
+                                               n_q_heads, n_kv_heads, head_dim, ctypes.c_float(scale), _ptr(out),
+                                               _ptr(lse), stream))
+
+
+XATTN_NOALLOC_SCRATCH_BYTES = 32 << 20
 
 
 def xattn_workspace_bytes(batch: int, q_len: int, n_q_heads: int, n_kv_heads: int, head_dim: int) -> int:

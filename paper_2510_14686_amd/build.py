@@ -19,7 +19,7 @@ INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 OBJ_DIR = os.path.join(_HERE, "_build")
 LIB_PATH = os.path.join(_HERE, "libxattn.so")
 HOSTTEST_LIB_PATH = os.path.join(_HERE, "libxattn_hosttest.so")
-SOURCES = ["xattn_kernels.hip", "xattn_mla.hip", "xattn_api.cpp", "xattn_error.cpp", "xtensor.cpp",
+SOURCES = ["xattn_kernels.hip", "xattn_mla.hip", "xattn_noalloc.hip", "xattn_api.cpp", "xattn_error.cpp", "xtensor.cpp",
            "vmm_hip.cpp", "xtensor_pool.cpp", "xbeam.cpp"]
 HOSTTEST_SOURCES = ["xattn_error.cpp", "xtensor_pool.cpp", "xbeam.cpp", os.path.join("host_test", "vmm_fake.cpp"),
                     os.path.join("host_test", "plan_shim.cpp")]
