@@ -530,6 +530,7 @@ def main():
     ap.add_argument("--beam", action="store_true", help="host-only: time the beam-search selection step (heap with early exit vs sorting everything)")
     ap.add_argument("--mla-layout", type=int, default=0, help="latent-KV kernel: 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave")
     ap.add_argument("--pv-mode", type=int, default=0, help="precision of the softmax weights in the value product, see XATTN_CFG_PV_MODE")
+    ap.add_argument("--xcd-skew", type=int, default=0, help="XATTN_CFG_XCD_SKEW: 0 default, n = (n - 1) per mille moved from the odd XCDs' parts to the even ones'")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB ten times (reads 1 GiB, writes 1 GiB per launch): "
                          "the known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -569,6 +570,7 @@ def main():
     xa.xattn_configure(xa.XATTN_CFG_PATH, args.path)
     xa.xattn_configure(xa.XATTN_CFG_PV_MODE, args.pv_mode)
     xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, args.mla_layout)
+    xa.xattn_configure(xa.XATTN_CFG_XCD_SKEW, args.xcd_skew)
     if args.xtensor:
         print(json.dumps({"xtensor_page_ops": xtensor_page_ops(), "decode_loop": decode_loop_bench()}), flush=True)
         return

@@ -1,5 +1,5 @@
 """MI355X-native decode attention over xTensor-style KV memory (libxattn.so + ctypes binding)."""
-from .binding import (XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_MLA_LAYOUT, XATTN_CFG_PATH, XATTN_CFG_PIECES, XATTN_CFG_PV_MODE, XATTN_CFG_TIMING, XTENSOR_CHUNK_BYTES, XattnError,  # noqa: F401
+from .binding import (XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_MLA_LAYOUT, XATTN_CFG_PATH, XATTN_CFG_PIECES, XATTN_CFG_PV_MODE, XATTN_CFG_TIMING, XATTN_CFG_XCD_SKEW, XTENSOR_CHUNK_BYTES, XattnError,  # noqa: F401
                       load_library, xattn_configure, xattn_decode, xattn_decode_noalloc, xattn_last_error, xattn_set_workspace, xattn_timing_read,
                       xattn_workspace_bytes, xtensor_chunk_order, xtensor_download, xtensor_map,
                       xtensor_physical_view, xtensor_unmap, xtensor_upload)

@@ -16,6 +16,7 @@ from . import build as _build
 
 XATTN_OK, XATTN_EINVAL, XATTN_EUNSUPPORTED, XATTN_ENOMEM, XATTN_EHIP = 0, -1, -2, -3, -4
 XATTN_CFG_PIECES, XATTN_CFG_MIN_PIECE_TOKENS, XATTN_CFG_TIMING, XATTN_CFG_PATH, XATTN_CFG_PV_MODE, XATTN_CFG_MLA_LAYOUT = 0, 1, 2, 3, 4, 5
+XATTN_CFG_XCD_SKEW = 6
 XTENSOR_CHUNK_BYTES = 2 << 20
 
 EXPORTS = ["xattn_last_error", "xattn_decode", "xattn_decode_noalloc", "xattn_workspace_bytes", "xattn_set_workspace",

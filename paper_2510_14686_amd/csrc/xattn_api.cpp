@@ -9,6 +9,7 @@
 #include "xattn_hip_error.h"
 #include "xattn_host.h"
 #include "xattn_kernels.h"
+#include "xattn_plan.h"
 
 namespace xattn {
 
@@ -48,6 +49,7 @@ int g_cfg_timing = 0;
 int g_cfg_path = 0;
 int g_cfg_pv_mode = 0;
 int g_cfg_mla_layout = 0;
+int g_cfg_xcd_skew = 0;              // 0 = the kernel's default, n > 0 = n - 1 per mille
 
 constexpr int kMaxTimedCalls = 4096;
 std::vector<hipEvent_t> g_events;     // three per timed call, created on demand, reused across series
@@ -229,6 +231,7 @@ int decode_call(const char* who, FixedWorkspaceFn fixed_workspace, const void* q
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;      // one 16-key block at least
+    prm.xcd_skew = g_cfg_xcd_skew > 0 ? g_cfg_xcd_skew - 1 : kDefaultXcdSkewGqa;
     prm.path = g_cfg_path;
     prm.pv_mode = g_cfg_pv_mode;
 
@@ -263,6 +266,10 @@ int xattn_configure(int key, int value) {
         case XATTN_CFG_MLA_LAYOUT:
             if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: MLA layout %d is not 0, 1 or 2", value);
             g_cfg_mla_layout = value;
+            return XATTN_OK;
+        case XATTN_CFG_XCD_SKEW:
+            if (value > kMaxXcdSkew + 1) return fail(XATTN_EINVAL, "xattn_configure: XCD skew %d is not in [0, %d]", value, kMaxXcdSkew + 1);
+            g_cfg_xcd_skew = value;
             return XATTN_OK;
         case XATTN_CFG_PV_MODE:
             if (value > 2) return fail(XATTN_EINVAL, "xattn_configure: pv mode %d is not 0, 1 or 2", value);
@@ -367,6 +374,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     prm.n_pieces = n_pieces;
     prm.min_piece_tokens = g_cfg_min_piece > 0 ? g_cfg_min_piece : kDefaultMinPieceTokens;
     if (prm.min_piece_tokens < 16) prm.min_piece_tokens = 16;
+    prm.xcd_skew = g_cfg_xcd_skew > 0 ? g_cfg_xcd_skew - 1 : kDefaultXcdSkewMla;
     prm.layout = g_cfg_mla_layout;
     prm.weight_mode = g_cfg_pv_mode;
     hipEvent_t* events = nullptr;

@@ -108,6 +108,52 @@ struct WavePlan {
     int mine;                // stream positions of this lane's sequences
     int excl;                // stream positions before this lane's first sequence
 };
+// Lengths and base addresses of up to 64 consecutive sequences, one per lane: those around the
+// position a wave starts at, fetched in the same round trips as the plan, so that a segment's first
+// K/V loads do not wait for another two dependent loads (its length, then its pointers).
+struct SeqWindow {
+    int base, count;         // sequences base .. base + count - 1 are held
+    int len;                 // lane l: clamp_len(kv_lens[base + l])
+    u32x2_t k, v;            // lane l: k_ptrs[base + l], v_ptrs[base + l] (v unused by kernels with one pointer array)
+};
+
+__device__ __forceinline__ u32x2_t load_ptr_entry(const void* const* ptrs, int batch, int idx) {
+    const __amdgpu_buffer_rsrc_t r = make_rsrc(ptrs, (uint32_t)batch * 8u);
+    return __builtin_bit_cast(u32x2_t, __builtin_amdgcn_raw_buffer_load_b64(r, idx * 8, 0, 0));
+}
+__device__ __forceinline__ void window_load(SeqWindow& win, const int32_t* __restrict__ kv_lens, const void* const* k_ptrs,
+                                            const void* const* v_ptrs, int batch, int base, int count, int lane,
+                                            int seg_cost, int& positions) {
+    const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
+    const int idx = lane < count ? base + lane : batch;            // past the batch: reads 0
+    const int raw = (int)__builtin_amdgcn_raw_buffer_load_b32(rl, idx * 4, 0, 0);
+    win.k = load_ptr_entry(k_ptrs, batch, idx);
+    win.v = v_ptrs ? load_ptr_entry(v_ptrs, batch, idx) : u32x2_t{0u, 0u};
+    win.base = base;
+    win.count = count;
+    win.len = clamp_len(raw);
+    positions = stream_len(raw, seg_cost);
+}
+// Length and pointers of sequence b: from the window when it holds b, else from memory.  Wave-uniform.
+__device__ __forceinline__ int window_len(const SeqWindow& win, const int32_t* __restrict__ kv_lens, int b) {
+    const unsigned i = (unsigned)(b - win.base);
+    if (i < (unsigned)win.count) return __builtin_amdgcn_readlane(win.len, __builtin_amdgcn_readfirstlane((int)i));
+    return __builtin_amdgcn_readfirstlane(clamp_len(kv_lens[b]));
+}
+__device__ __forceinline__ const void* window_ptr(const SeqWindow& win, const u32x2_t& held, const void* const* ptrs, int b) {
+    const unsigned i = (unsigned)(b - win.base);
+    uint64_t a;
+    if (i < (unsigned)win.count) {
+        const int li = __builtin_amdgcn_readfirstlane((int)i);
+        a = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)held.x, li) |
+            ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)held.y, li) << 32);
+    } else {
+        const uint64_t m = (uint64_t)(uintptr_t)ptrs[b];
+        a = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)m) |
+            ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(m >> 32)) << 32);
+    }
+    return reinterpret_cast<const void*>((uintptr_t)a);
+}
 
 template <int kQuads>
 __device__ __forceinline__ int chunk_positions(__amdgpu_buffer_rsrc_t rl, int first, int seg_cost) {
@@ -122,8 +168,12 @@ __device__ __forceinline__ int chunk_positions(__amdgpu_buffer_rsrc_t rl, int fi
     return sum;
 }
 
-__device__ __forceinline__ WavePlan wave_plan(const int32_t* __restrict__ kv_lens, int batch, int n_pieces,
-                                              int min_piece, int seg_cost, int lane) {
+// win (optional): with at most 64 sequences (one per lane) the window is filled here, in the plan's own
+// round trip.  (It pays in the latent-KV kernel, whose workgroups wait at a barrier for the first block
+// of a segment; the GQA kernel's independent waves hide those two loads and only lose registers to it.)
+__device__ __forceinline__ WavePlan wave_plan(const int32_t* __restrict__ kv_lens, const void* const* k_ptrs,
+                                              const void* const* v_ptrs, int batch, int n_pieces, int min_piece,
+                                              int seg_cost, int xcd_skew, int lane, SeqWindow* win) {
     WavePlan wp;
     int lg = 0;
     while ((64 << lg) < batch) ++lg;                       // wave-uniform: batch is a kernel argument
@@ -132,8 +182,15 @@ __device__ __forceinline__ WavePlan wave_plan(const int32_t* __restrict__ kv_len
     const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
     const int first = lane << lg;
     int mine;
+    if (win) {
+        win->base = 0;
+        win->count = 0;
+    }
     switch (lg) {
-        case 0: mine = stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4, 0, 0), seg_cost); break;
+        case 0:
+            if (win) window_load(*win, kv_lens, k_ptrs, v_ptrs, batch, 0, batch, lane, seg_cost, mine);
+            else mine = stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4, 0, 0), seg_cost);
+            break;
         case 1: mine = stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4, 0, 0), seg_cost) +
                        stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, first * 4 + 4, 0, 0), seg_cost); break;
         case 2: mine = chunk_positions<1>(rl, first, seg_cost); break;
@@ -145,20 +202,32 @@ __device__ __forceinline__ WavePlan wave_plan(const int32_t* __restrict__ kv_len
     const int incl = wave_incl_scan_i(mine, lane);
     wp.mine = mine;
     wp.excl = incl - mine;
-    wp.pl = plan_for_total(__builtin_amdgcn_readlane(incl, 63), n_pieces, min_piece, seg_cost);
+    wp.pl = plan_for_total(__builtin_amdgcn_readlane(incl, 63), n_pieces, min_piece, seg_cost, xcd_skew);
     return wp;
 }
 
 // The sequence b that holds stream position s (0 <= s < N) and the offset j of s within that
-// sequence's L + seg_cost positions.  Both wave-uniform.
-__device__ __forceinline__ void wave_locate(const WavePlan& wp, const int32_t* __restrict__ kv_lens, int batch, int s,
-                                            int lane, int& b, int& j) {
+// sequence's L + seg_cost positions.  Both wave-uniform.  With more than 64 sequences the window is
+// filled here with the located chunk.
+__device__ __forceinline__ void wave_locate(const WavePlan& wp, const int32_t* __restrict__ kv_lens, const void* const* k_ptrs,
+                                            const void* const* v_ptrs, int batch, int s, int lane, SeqWindow* win, int& b,
+                                            int& j) {
     const unsigned long long hit = __ballot(s >= wp.excl && s < wp.excl + wp.mine);
     const int ln = hit ? __builtin_ctzll(hit) : 0;
-    const int base = ln << wp.chunk_log2;
     const int off = s - __shfl(wp.excl, ln, 64);
-    const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
-    const int v = lane < wp.chunk ? stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, (base + lane) * 4, 0, 0), wp.pl.seg_cost) : 0;
+    if (wp.chunk_log2 == 0) {
+        b = __builtin_amdgcn_readfirstlane(ln);
+        j = __builtin_amdgcn_readfirstlane(off);
+        return;
+    }
+    const int base = ln << wp.chunk_log2;
+    int v;
+    if (win) {
+        window_load(*win, kv_lens, k_ptrs, v_ptrs, batch, base, wp.chunk, lane, wp.pl.seg_cost, v);
+    } else {
+        const __amdgpu_buffer_rsrc_t rl = make_rsrc(kv_lens, (uint32_t)batch * 4u);
+        v = lane < wp.chunk ? stream_len(__builtin_amdgcn_raw_buffer_load_b32(rl, (base + lane) * 4, 0, 0), wp.pl.seg_cost) : 0;
+    }
     const int incl = wave_incl_scan_i(v, lane);
     const unsigned long long hit2 = __ballot(off >= incl - v && off < incl);
     const int ln2 = hit2 ? __builtin_ctzll(hit2) : 0;

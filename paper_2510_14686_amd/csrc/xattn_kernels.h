@@ -8,6 +8,12 @@
 namespace xattn {
 
 constexpr int kHeadDim = 128;
+// Default share (per mille) moved from the odd-numbered XCDs' parts of the token stream to the
+// even-numbered ones: on MI355X the odd XCDs need about 7 % longer for the same bytes (measured per
+// wave with clock stamps on several machines; rotating the data among the XCDs moves nothing), so
+// equal parts leave the even XCDs idle at the end of the kernel.
+constexpr int kDefaultXcdSkewGqa = 32;
+constexpr int kDefaultXcdSkewMla = 0;
 constexpr int kMaxWavesPerBlock = 8;   // one wave per KV head, up to 8 KV heads per workgroup
 
 // Workspace header: per sequence two int32 words, (first partial slot, number of segments), written
@@ -27,6 +33,7 @@ struct DecodeParams {
     int32_t* meta;                   // int32 [batch, 2]
     int n_pieces;                    // pieces the token stream is cut into (upper bound on active ones)
     int min_piece_tokens;
+    int xcd_skew;                    // per mille: share taken from the odd XCDs' parts of the stream and given to the even ones
     int path;                        // kPathAuto, kPathVector or kPathMatrix
     int pv_mode;                     // matrix path: kPvBf16x2, kPvFp32 or kPvBf16
 };
@@ -63,6 +70,7 @@ struct MlaParams {
     float* part_ml;                  // fp32 [slots, q_len * n_heads, 4]: (max, sum, sum of rounded weights, 1 / scale)
     int32_t* meta;                   // int32 [batch, 2]
     int n_pieces, min_piece_tokens;
+    int xcd_skew;                    // as in DecodeParams
     int layout;                      // 0 automatic, 1 one 16-row tile per wave, 2 two tiles per wave
     int weight_mode;                 // softmax weights in the value product: 0 default (hi + lo bf16 parts where a key
                                      // dominates, one bf16 elsewhere), 1 hi + lo everywhere, 2 one bf16 everywhere

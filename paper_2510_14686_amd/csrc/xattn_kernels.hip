@@ -38,6 +38,8 @@ namespace {
 struct Segment {
     int b, L;            // sequence and its length
     int j0, j1;          // keys [j0, j1) of the sequence
+    const void* kp;      // the sequence's K and V ranges
+    const void* vp;
     int slot;            // partial-result slot (piece + sequence index)
     bool whole;          // the segment is the whole sequence: write the final result
     int kvh;             // this wave's KV head
@@ -136,8 +138,8 @@ __device__ __forceinline__ void vector_segment(const DecodeParams& prm, const Se
     const int sub = lane >> 4, ds = lane & 15;
     const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
     const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
-    const __amdgpu_buffer_rsrc_t rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
-    const __amdgpu_buffer_rsrc_t rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
+    const __amdgpu_buffer_rsrc_t rk = make_rsrc(seg.kp, seq_bytes(prm, seg.L));
+    const __amdgpu_buffer_rsrc_t rv = make_rsrc(seg.vp, seq_bytes(prm, seg.L));
     const uint32_t voffset = (uint32_t)sub * row_stride + (uint32_t)seg.kvh * kRowBytes + ds * 16;
 
     // Q rows of this KV head: row r <-> (token t = r / G, head kvh*G + r % G); lane takes columns ds*8..+8.
@@ -379,8 +381,8 @@ __device__ __forceinline__ void matrix_begin(MatrixCtx& c, const DecodeParams& p
     const int G = prm.group, T = prm.q_len, Hq = prm.n_q_heads;
     const uint32_t row_stride = (uint32_t)prm.n_kv_heads * kRowBytes;
     c.seg = seg;
-    c.rk = make_rsrc(prm.k_ptrs[seg.b], seq_bytes(prm, seg.L));
-    c.rv = make_rsrc(prm.v_ptrs[seg.b], seq_bytes(prm, seg.L));
+    c.rk = make_rsrc(seg.kp, seq_bytes(prm, seg.L));
+    c.rv = make_rsrc(seg.vp, seq_bytes(prm, seg.L));
     c.voffset = (uint32_t)(4 * kb) * row_stride + (uint32_t)seg.kvh * kRowBytes + n * 16;
     load_regs(c.first, c.rk, c.rv, c.voffset, row_stride, seg.j0);
     // Row n of the tile <-> (token t, head kvh*G + g); rows past n_rows are zero padding.
@@ -516,7 +518,8 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     const int wave = threadIdx.x >> 6;
     const int kvh = blockIdx.z * kMaxWavesPerBlock + wave;
     if (kvh >= prm.n_kv_heads) return;
-    const WavePlan wp = wave_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kGqaSegCost, lane);
+    const WavePlan wp = wave_plan(prm.kv_lens, nullptr, nullptr, prm.batch, prm.n_pieces, prm.min_piece_tokens, kGqaSegCost,
+                                  prm.xcd_skew, lane, nullptr);
     const Plan& pl = wp.pl;
 
     // Piece index: consecutive workgroups go to different XCDs, so give each XCD one contiguous
@@ -535,7 +538,7 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
     if (!active) return;
 
     Walk walk;
-    wave_locate(wp, prm.kv_lens, prm.batch, s0, lane, walk.b, walk.j);
+    wave_locate(wp, prm.kv_lens, nullptr, nullptr, prm.batch, s0, lane, nullptr, walk.b, walk.j);
     walk.remaining = s1 - s0;
 
     const int rows_total = prm.group * prm.q_len;
@@ -551,6 +554,8 @@ __global__ __launch_bounds__(512) void split_decode_kernel(DecodeParams prm) {
             return false;
         out = seg;
         out.b = ps.b;
+        out.kp = prm.k_ptrs[ps.b];
+        out.vp = prm.v_ptrs[ps.b];
         out.L = ps.L;
         out.j0 = ps.j0;
         out.j1 = ps.j1;

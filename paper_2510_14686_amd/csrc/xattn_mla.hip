@@ -32,7 +32,7 @@
 //     8 keys per lane) fetched with LDS transposing reads.  A weight enters the product as one bf16
 //     where it is small against the row's sum, and as hi + lo bf16 parts (two MFMAs, 16 significant
 //     bits) where it is not: in the first kExactBlocks blocks of every segment, whose keys' share of
-//     the final sum is not yet known, and in any later block that holds a key with at least 1/8 of
+//     the final sum is not yet known, and in any later block that holds a key with at least 1/4 of
 //     the row's running sum.  The output is normalised by the sum of the weights as they entered
 //     the product.  (Rounding every weight to one bf16 costs nothing on diffuse rows, where the
 //     errors average out; where a few keys carry the row, outputs are large enough for bf16 output
@@ -75,9 +75,8 @@ constexpr int kQLdsWave = (kQSteps - kQRegSteps) * 1024;   // per 16-row tile: o
 constexpr int kQAhead = 2;                       // key fragments in flight ahead of the MFMAs, in steps
 constexpr int kVAhead = 2;                       // value fragments in flight ahead of the MFMAs, in tile pairs
 constexpr int kColTiles = kDv / 16;              // 32 tiles of 16 value columns
-constexpr int kOutCols = 64;                     // epilogue: 16 rows x 64 fp32 columns at a time, padded
-constexpr int kOutPitch = kOutCols * 4 + 16;
-constexpr int kLdsOutPerWave = 16 * kOutPitch;
+constexpr int kStagePitch = (kDv / 2) * 2 + 16;  // epilogue: 16 rows x 256 16-bit columns at a time per wave, padded rows
+constexpr int kStageWave = 16 * kStagePitch;     // 8448 bytes
 // A segment's fixed work (first block's latency, Q, output staging and stores; measured: workgroups
 // with two segments finish 13 us later than their token count says) in units of one token's share of
 // the block loop (2.3 us per 32 tokens).
@@ -88,7 +87,7 @@ constexpr int kLoNever = 0;                      // one bf16 per weight everywhe
 constexpr int kLoAlways = 1;                     // hi + lo bf16 parts everywhere
 constexpr int kLoDynamic = 2;                    // hi + lo parts only in blocks with a dominant key
 constexpr int kExactBlocks = 4;                  // default mode: the first blocks of a segment run as kLoAlways
-constexpr float kDominantShare = 8.0f;           // a key is dominant from 1 / 8 of the row's running sum
+constexpr float kDominantShare = 4.0f;           // a key is dominant from 1 / 4 of the row's running sum
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
@@ -399,14 +398,15 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
 template <int NW, int RT, int kMode>
 __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     __shared__ __attribute__((aligned(16))) char lds_c[kStages * kLdsBlock];
-    // Per wave and tile: the Q chunks of steps kQRegSteps.. (each lane reads back what it wrote); the
-    // same bytes stage the output at the end of a segment, when Q is no longer needed.
+    // Per wave and tile: the Q chunks of steps kQRegSteps.. (each lane reads back what it wrote).
     __shared__ __attribute__((aligned(16))) char lds_q[NW * RT * kQLdsWave];
-    static_assert(kQLdsWave >= kLdsOutPerWave, "output staging must fit the wave's Q area");
+    static_assert(NW * kStageWave <= kStages * kLdsBlock, "output staging must fit the block buffers");
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int kb = lane >> 4, n = lane & 15;
     const int T = prm.q_len, H = prm.n_heads, rows_total = T * H;
-    const WavePlan wp = wave_plan(prm.kv_lens, prm.batch, prm.n_pieces, prm.min_piece_tokens, kMlaSegCost, lane);
+    SeqWindow win;
+    const WavePlan wp = wave_plan(prm.kv_lens, prm.c_ptrs, nullptr, prm.batch, prm.n_pieces, prm.min_piece_tokens, kMlaSegCost,
+                                  prm.xcd_skew, lane, &win);
     const Plan& pl = wp.pl;
     const int per_xcd = (pl.n_pieces + 7) >> 3;
     // Workgroup ids go round-robin over the 8 XCDs.  Of an XCD's workgroups, consecutive ones are the
@@ -428,13 +428,13 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
     if (!active) return;       // the whole workgroup: every wave computed the same plan
 
     Walk walk;
-    wave_locate(wp, prm.kv_lens, prm.batch, s0, lane, walk.b, walk.j);
+    wave_locate(wp, prm.kv_lens, prm.c_ptrs, nullptr, prm.batch, s0, lane, &win, walk.b, walk.j);
     walk.remaining = s1 - s0;
 
     // Row n of tile rt of this wave: row index within the sequence's T * H rows.
     const int wave_row0 = row_group * (16 * RT * NW) + wave * (16 * RT);
     char* q_lds = lds_q + wave * (RT * kQLdsWave) + lane * 16;
-    char* out_lds = lds_q + wave * (RT * kQLdsWave);
+    char* stage = lds_c + wave * kStageWave;
     const DmaLane dma = dma_lane(lane);
     const int my_loads = (kDmaPerBlock - wave + NW - 1) / NW;      // block loads this wave issues per block
     const int qk_off = n * kPitch + kb * 16;
@@ -448,12 +448,12 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
 
     PieceSeg ps;
     while (next_segment(walk, prm.batch, pl.seg_cost,
-                        [&](int bb) { return __builtin_amdgcn_readfirstlane(clamp_len(prm.kv_lens[bb])); }, ps)) {
+                        [&](int bb) { return window_len(win, prm.kv_lens, bb); }, ps)) {
         const int b = ps.b, L = ps.L, j0 = ps.j0, j1 = ps.j1;
         const bool whole = ps.whole;
         const long slot = (long)p + b;
         const unsigned long long cbytes = (unsigned long long)L * kRowB;
-        const uint64_t caddr = (uint64_t)(uintptr_t)prm.c_ptrs[b];
+        const uint64_t caddr = (uint64_t)(uintptr_t)window_ptr(win, win.k, prm.c_ptrs, b);
         // raw buffer descriptor: base, no stride, bytes, 32-bit raw format
         const u32x4_t rc = {(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)caddr),
                             (uint32_t)__builtin_amdgcn_readfirstlane((int)((uint32_t)(caddr >> 32) & 0xffffu)),
@@ -518,10 +518,8 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         int blk = 0;
         for (; blk < n_exact; ++blk) step(blk, std::integral_constant<int, kLoAlways>());
         for (; blk < n_blocks; ++blk) step(blk, std::integral_constant<int, kMode == 0 ? kLoDynamic : kLoNever>());
-        __syncthreads();          // the next segment's first block reuses buffer 0
+        __syncthreads();          // everyone is done with the block buffers: they stage the output now
 
-        // Store, 64 columns at a time through this wave's LDS so that a store instruction writes whole
-        // 256-byte pieces of rows.
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             const float l = st[rt].l;
@@ -545,29 +543,27 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 inv_scale = amax > 0.0f ? 1.0f / sc : 0.0f;
             }
             const int tile_row0 = wave_row0 + 16 * rt;
+            // Rounded to 16 bits (bf16 results, fp16 partial rows), half a row at a time through the
+            // block buffers, which are free between the segment's last block and the next segment's
+            // first: two rounds per tile, each store instruction writing two whole 512-byte half rows.
+            uint16_t* dst = whole ? prm.out + (long)b * rows_total * kDv : prm.part_o + slot * rows_total * kDv;
 #pragma unroll
-            for (int g = 0; g < kDv / kOutCols; ++g) {
+            for (int h = 0; h < 2; ++h) {
 #pragma unroll
-                for (int c = 0; c < kOutCols / 16; ++c) {
-                    const f32x4_t o = st[rt].o[(kOutCols / 16) * g + c] * sc;
-                    *reinterpret_cast<float4*>(out_lds + n * kOutPitch + (16 * c + 4 * kb) * 4) = make_float4(o[0], o[1], o[2], o[3]);
+                for (int c = 0; c < kColTiles / 2; ++c) {
+                    const f32x4_t o = st[rt].o[(kColTiles / 2) * h + c] * sc;
+                    uint2 w;
+                    w.x = whole ? pack_bf16(o[0], o[1]) : pack_f16(o[0], o[1]);
+                    w.y = whole ? pack_bf16(o[2], o[3]) : pack_f16(o[2], o[3]);
+                    *reinterpret_cast<uint2*>(stage + n * kStagePitch + (16 * c + 4 * kb) * 2) = w;
                 }
                 fence();
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {          // 4 rows x 64 fp32 columns per instruction
-                    const int rl = 4 * i + (lane >> 4), rr = tile_row0 + rl, col = g * kOutCols + (lane & 15) * 4;
+                for (int i = 0; i < 8; ++i) {          // 2 rows x 256 columns per instruction
+                    const int rl = 2 * i + (lane >> 5), rr = tile_row0 + rl;
                     if (rr < rows_total) {
-                        const float4 w = *reinterpret_cast<const float4*>(out_lds + rl * kOutPitch + (lane & 15) * 16);
-                        uint2 o2;
-                        if (whole) {
-                            o2.x = pack_bf16(w.x, w.y);
-                            o2.y = pack_bf16(w.z, w.w);
-                            *reinterpret_cast<uint2*>(prm.out + ((long)b * rows_total + rr) * kDv + col) = o2;
-                        } else {
-                            o2.x = pack_f16(w.x, w.y);
-                            o2.y = pack_f16(w.z, w.w);
-                            *reinterpret_cast<uint2*>(prm.part_o + (slot * rows_total + rr) * kDv + col) = o2;
-                        }
+                        const uint4 w = *reinterpret_cast<const uint4*>(stage + rl * kStagePitch + (lane & 31) * 16);
+                        *reinterpret_cast<uint4*>(dst + (long)rr * kDv + h * (kDv / 2) + (lane & 31) * 8) = w;
                     }
                 }
                 fence();
@@ -581,6 +577,7 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 }
             }
         }
+        __syncthreads();          // the next segment's first block goes to buffer 0, which staged output until here
     }
 }
 
@@ -620,7 +617,8 @@ __global__ __launch_bounds__(256) void mla_merge_kernel(MlaParams prm) {
         for (int u = 0; u < 4; ++u) {
             const int s = s0 + u < n ? s0 + u : n - 1;
             a[u] = ml[s * rows_total];
-            o[u] = po[s * po_stride];
+            const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(&po[s * po_stride]));   // read once
+            o[u] = make_uint4(t.x, t.y, t.z, t.w);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {

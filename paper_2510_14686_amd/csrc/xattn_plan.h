@@ -33,37 +33,70 @@ struct Plan {
     int total;      // N: positions of the whole stream
     int n_pieces;   // pieces in use: min(launched pieces, N / minimum piece size), at least 1
     int seg_cost;
+    int xcd_skew;   // per mille; see piece_bound
 };
+constexpr int kMaxXcdSkew = 200;
 
 XATTN_HD int clamp_len(int v) { return v > 0 ? v : 0; }
 // Stream positions of a sequence of `len` tokens (any sign).
 XATTN_HD int stream_len(int len, int seg_cost) { return len > 0 ? len + seg_cost : 0; }
 
-XATTN_HD Plan plan_for_total(int total, int n_pieces, int min_piece, int seg_cost) {
+XATTN_HD Plan plan_for_total(int total, int n_pieces, int min_piece, int seg_cost, int xcd_skew = 0) {
     int n = total / (min_piece > 0 ? min_piece : 1);
     n = n < 1 ? 1 : n;
     Plan pl;
     pl.total = total;
     pl.n_pieces = n < n_pieces ? n : n_pieces;
     pl.seg_cost = seg_cost;
+    // the skew needs the eight XCD parts to hold the same number of pieces, of a few blocks at least
+    const bool can_skew = xcd_skew > 0 && pl.n_pieces % 8 == 0 && total / pl.n_pieces >= 4 * kPlanRound;
+    pl.xcd_skew = can_skew ? (xcd_skew < kMaxXcdSkew ? xcd_skew : kMaxXcdSkew) : 0;
     return pl;
 }
 
-// Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): floor(p * N / n_pieces) rounded
-// to the nearest multiple of the 16-key block, so every piece is within 16 positions of N / n_pieces
-// and all are used.  32-bit arithmetic only: p * N / n = p * (N / n) + p * (N % n) / n, and
-// p * (N % n) < n^2 <= 2^32.
+// floor(i * span / m) in 32-bit arithmetic: i * (span / m) + i * (span % m) / m, with i <= m <= 65536
+// so that i * (span % m) < m^2 <= 2^32.
+XATTN_HD uint32_t scaled_index(uint32_t i, uint32_t span, uint32_t m) { return i * (span / m) + i * (span % m) / m; }
+
+// The chip's eight XCDs do not stream at the same rate: measured on MI355X, the odd-numbered ones
+// take about 7 % longer than the even-numbered ones for the same bytes, whatever data they are given.
+// The kernels hand XCD x the pieces x * n / 8 .. (x + 1) * n / 8 - 1 (consecutive workgroup ids go to
+// consecutive XCDs), so the stream is first cut into eight XCD parts, part x starting at
+// N * (x + (x odd ? skew : 0)) / 8 (skew = xcd_skew / 1000: even parts are longer by that fraction, odd
+// parts shorter), and every part into n / 8 equal pieces.  xcd_skew = 0: eight equal parts.
+XATTN_HD uint32_t xcd_part_start(const Plan& pl, int x) {
+    return (uint32_t)(((uint64_t)(uint32_t)pl.total * (uint32_t)(1000 * x + ((x & 1) ? pl.xcd_skew : 0))) / 8000u);
+}
+
+// Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): floor(p * N / n_pieces) (or its
+// skewed counterpart) rounded to the nearest multiple of the 16-key block, so every piece is within
+// 16 positions of its exact share and all are used.
 XATTN_HD int piece_bound(const Plan& pl, int p) {
     if (p >= pl.n_pieces) return pl.total;
-    const uint32_t n = (uint32_t)pl.n_pieces, q = (uint32_t)pl.total / n, r = (uint32_t)pl.total % n;
-    const uint32_t x = (uint32_t)p * q + (uint32_t)p * r / n;
+    uint32_t x;
+    if (pl.xcd_skew == 0) {
+        x = scaled_index((uint32_t)p, (uint32_t)pl.total, (uint32_t)pl.n_pieces);
+    } else {
+        const uint32_t m = (uint32_t)pl.n_pieces / 8u, part = (uint32_t)p / m;
+        const uint32_t a = xcd_part_start(pl, (int)part), b = xcd_part_start(pl, (int)part + 1);
+        x = a + scaled_index((uint32_t)p - part * m, b - a, m);
+    }
     const uint32_t rounded = (x + kPlanRound / 2) / kPlanRound * kPlanRound;
     return rounded < (uint32_t)pl.total ? (int)rounded : pl.total;
 }
 
 // The piece that owns stream position x (0 <= x < N): an estimate, corrected against piece_bound.
 XATTN_HD int piece_of(const Plan& pl, int x) {
-    int p = (int)((float)x * (float)pl.n_pieces / (float)pl.total);
+    int p;
+    if (pl.xcd_skew == 0) {
+        p = (int)((float)x * (float)pl.n_pieces / (float)pl.total);
+    } else {
+        const int m = pl.n_pieces / 8;
+        int part = 0;
+        while (part < 7 && xcd_part_start(pl, part + 1) <= (uint32_t)x) ++part;
+        const uint32_t a = xcd_part_start(pl, part), b = xcd_part_start(pl, part + 1);
+        p = part * m + (int)((float)((uint32_t)x - a) * (float)m / (float)(b - a));
+    }
     p = p < 0 ? 0 : (p > pl.n_pieces - 1 ? pl.n_pieces - 1 : p);
     while (p + 1 < pl.n_pieces && piece_bound(pl, p + 1) <= x) ++p;
     while (p > 0 && piece_bound(pl, p) > x) --p;

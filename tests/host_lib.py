@@ -25,11 +25,11 @@ def load(path=None):
     lib.xtensor_test_fail_next.argtypes = [i32, i32]
     lib.xtensor_test_fake_counts.restype = i32
     lib.xtensor_test_fake_counts.argtypes = [ctypes.POINTER(sz)] * 3
-    for name, args in (("xattn_test_plan", [vp, i32, i32, i32, i32, vp]),
-                       ("xattn_test_piece_bounds", [vp, i32, i32, i32, i32, vp]),
-                       ("xattn_test_piece_of", [vp, i32, i32, i32, i32, i32]),
-                       ("xattn_test_piece_segments", [vp, i32, i32, i32, i32, i32, vp, i32]),
-                       ("xattn_test_meta", [vp, i32, i32, i32, i32, vp])):
+    for name, args in (("xattn_test_plan", [vp, i32, i32, i32, i32, i32, vp]),
+                       ("xattn_test_piece_bounds", [vp, i32, i32, i32, i32, i32, vp]),
+                       ("xattn_test_piece_of", [vp, i32, i32, i32, i32, i32, i32]),
+                       ("xattn_test_piece_segments", [vp, i32, i32, i32, i32, i32, i32, vp, i32]),
+                       ("xattn_test_meta", [vp, i32, i32, i32, i32, i32, vp])):
         fn = getattr(lib, name)
         fn.restype = i32
         fn.argtypes = args
@@ -68,39 +68,39 @@ def _lens(kv_lens):
     return np.ascontiguousarray(kv_lens, dtype=np.int32)
 
 
-def plan(kv_lens, n_pieces, min_piece, seg_cost):
+def plan(kv_lens, n_pieces, min_piece, seg_cost, skew=0):
     """(N, pieces in use); N = -1 and pieces = -1 beyond the 32-bit limit."""
     kv = _lens(kv_lens)
     total = ctypes.c_int32()
-    n = load().xattn_test_plan(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, ctypes.addressof(total))
+    n = load().xattn_test_plan(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, skew, ctypes.addressof(total))
     return int(total.value), n
 
 
-def piece_bounds(kv_lens, n_pieces, min_piece, seg_cost):
+def piece_bounds(kv_lens, n_pieces, min_piece, seg_cost, skew=0):
     kv = _lens(kv_lens)
     out = np.zeros(n_pieces + 2, np.int32)
-    n = load().xattn_test_piece_bounds(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, out.ctypes.data)
+    n = load().xattn_test_piece_bounds(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, skew, out.ctypes.data)
     assert n >= 1
     return out[:n + 1].copy()
 
 
-def piece_of(kv_lens, n_pieces, min_piece, seg_cost, position):
+def piece_of(kv_lens, n_pieces, min_piece, seg_cost, position, skew=0):
     kv = _lens(kv_lens)
-    return load().xattn_test_piece_of(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, position)
+    return load().xattn_test_piece_of(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, skew, position)
 
 
-def piece_segments(kv_lens, n_pieces, min_piece, seg_cost, p, max_segs=8192):
+def piece_segments(kv_lens, n_pieces, min_piece, seg_cost, p, max_segs=8192, skew=0):
     """Rows (b, j0, j1, slot, whole) of piece p."""
     kv = _lens(kv_lens)
     out = np.zeros((max_segs, 5), np.int32)
-    n = load().xattn_test_piece_segments(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, p, out.ctypes.data, max_segs)
+    n = load().xattn_test_piece_segments(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, skew, p, out.ctypes.data, max_segs)
     assert 0 <= n <= max_segs
     return out[:n].copy()
 
 
-def meta(kv_lens, n_pieces, min_piece, seg_cost):
+def meta(kv_lens, n_pieces, min_piece, seg_cost, skew=0):
     """int32 [batch, 2]: (first partial slot, number of segments) per sequence."""
     kv = _lens(kv_lens)
     out = np.zeros((len(kv), 2), np.int32)
-    assert load().xattn_test_meta(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, out.ctypes.data) == 0
+    assert load().xattn_test_meta(kv.ctypes.data, len(kv), n_pieces, min_piece, seg_cost, skew, out.ctypes.data) == 0
     return out

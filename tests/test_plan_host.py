@@ -29,11 +29,11 @@ CASES = list(_cases())
 PARTITIONS = [(256, 64), (1, 16), (8, 16), (37, 48), (1024, 16), (65536, 16)]
 
 
-def _all_segments(lens, n_pieces, min_piece, cost):
-    total, used = host_lib.plan(lens, n_pieces, min_piece, cost)
+def _all_segments(lens, n_pieces, min_piece, cost, skew=0):
+    total, used = host_lib.plan(lens, n_pieces, min_piece, cost, skew)
     rows = []
     for p in range(used):
-        for b, j0, j1, slot, whole in host_lib.piece_segments(lens, n_pieces, min_piece, cost, p):
+        for b, j0, j1, slot, whole in host_lib.piece_segments(lens, n_pieces, min_piece, cost, p, skew=skew):
             rows.append((p, b, j0, j1, slot, whole))
     return total, used, rows
 
@@ -63,14 +63,14 @@ def test_pieces_tile_the_stream_and_balance(name, lens, n_pieces, min_piece, cos
             assert host_lib.piece_of(lens, n_pieces, min_piece, cost, x) == int(np.searchsorted(bounds, x, side="right")) - 1
 
 
-@pytest.mark.parametrize("cost", [0, GQA_COST, MLA_COST])
+@pytest.mark.parametrize("cost,skew", [(0, 0), (GQA_COST, 0), (MLA_COST, 0), (GQA_COST, 32), (MLA_COST, 200)])
 @pytest.mark.parametrize("n_pieces,min_piece", PARTITIONS[:5])
 @pytest.mark.parametrize("name,lens", CASES, ids=[c[0] for c in CASES])
-def test_every_token_is_in_exactly_one_segment(name, lens, n_pieces, min_piece, cost):
+def test_every_token_is_in_exactly_one_segment(name, lens, n_pieces, min_piece, cost, skew):
     lens = np.asarray(lens, np.int64)
     B = len(lens)
-    total, used, rows = _all_segments(lens, n_pieces, min_piece, cost)
-    bounds = host_lib.piece_bounds(lens, n_pieces, min_piece, cost)
+    total, used, rows = _all_segments(lens, n_pieces, min_piece, cost, skew)
+    bounds = host_lib.piece_bounds(lens, n_pieces, min_piece, cost, skew)
     covered = {b: [] for b in range(B)}
     slots = set()
     tokens_of_piece = np.zeros(used, np.int64)
@@ -96,13 +96,13 @@ def test_every_token_is_in_exactly_one_segment(name, lens, n_pieces, min_piece, 
     assert int(tokens_of_piece.sum()) == int(lens[lens > 0].sum())
 
 
-@pytest.mark.parametrize("cost", [GQA_COST, MLA_COST])
+@pytest.mark.parametrize("cost,skew", [(GQA_COST, 0), (MLA_COST, 0), (GQA_COST, 32), (MLA_COST, 200)])
 @pytest.mark.parametrize("n_pieces,min_piece", PARTITIONS[:5])
 @pytest.mark.parametrize("name,lens", CASES, ids=[c[0] for c in CASES])
-def test_segment_table_for_the_merge_equals_the_walk(name, lens, n_pieces, min_piece, cost):
+def test_segment_table_for_the_merge_equals_the_walk(name, lens, n_pieces, min_piece, cost, skew):
     lens = np.asarray(lens, np.int64)
-    total, used, rows = _all_segments(lens, n_pieces, min_piece, cost)
-    meta = host_lib.meta(lens, n_pieces, min_piece, cost)
+    total, used, rows = _all_segments(lens, n_pieces, min_piece, cost, skew)
+    meta = host_lib.meta(lens, n_pieces, min_piece, cost, skew)
     for b in range(len(lens)):
         mine = [r for r in rows if r[1] == b]
         first_slot, n_seg = int(meta[b, 0]), int(meta[b, 1])
@@ -112,20 +112,53 @@ def test_segment_table_for_the_merge_equals_the_walk(name, lens, n_pieces, min_p
             assert (n_seg == 1) == bool(mine[0][5]), "exactly the unsplit sequences are finished by the decode kernel"
 
 
+@pytest.mark.parametrize("skew", [1, 32, 200])
+@pytest.mark.parametrize("n_pieces,min_piece", [(256, 64), (8, 16), (1024, 16), (65536, 16), (37, 48)])
+@pytest.mark.parametrize("name,lens", CASES, ids=[c[0] for c in CASES])
+def test_unequal_xcd_parts(name, lens, n_pieces, min_piece, skew):
+    """With a skew the stream is cut into eight XCD parts, the even ones longer and the odd ones shorter
+    by skew / 1000, each cut into equal pieces; the pieces still tile the stream and piece_of inverts
+    the bounds.  Too few or too small pieces switch the skew off."""
+    lens = np.asarray(lens, np.int64)
+    N = int(sum(L + GQA_COST for L in lens if L > 0))
+    total, used = host_lib.plan(lens, n_pieces, min_piece, GQA_COST, skew)
+    assert total == N and used == max(1, min(n_pieces, N // min_piece))
+    bounds = host_lib.piece_bounds(lens, n_pieces, min_piece, GQA_COST, skew).astype(np.int64)
+    assert bounds[0] == 0 and bounds[-1] == N and len(bounds) == used + 1
+    sizes = np.diff(bounds)
+    if N == 0:
+        return
+    assert np.all(sizes > 0) and np.all(bounds[:-1] % 16 == 0)
+    skewed = used % 8 == 0 and N // used >= 64
+    if skewed:
+        m = used // 8
+        for x in range(8):
+            want = N / used * (1 + skew / 1000.0 * (1 if x % 2 == 0 else -1))
+            assert np.all(np.abs(sizes[x * m:(x + 1) * m] - want) <= 17), "XCD part %d" % x
+            assert abs(bounds[x * m] - N * (x + (skew / 1000.0 if x % 2 else 0)) / 8) <= 9
+    else:
+        assert np.array_equal(bounds, host_lib.piece_bounds(lens, n_pieces, min_piece, GQA_COST, 0))
+    rng = np.random.RandomState(4)
+    xs = set(int(x) for x in rng.randint(0, N, size=64)) | set(int(b) for b in bounds[:-1]) | set(int(b) - 1 for b in bounds[1:])
+    for x in sorted(xs):
+        if 0 <= x < N:
+            assert host_lib.piece_of(lens, n_pieces, min_piece, GQA_COST, x, skew) == int(np.searchsorted(bounds, x, side="right")) - 1
+
+
 def test_stream_positions_up_to_the_32_bit_limit():
     """N just below 2^31 with the largest piece count: the 32-bit products of piece_bound do not wrap;
     beyond 2^31 - 1 the documented limit is reported, not wrapped."""
     lens = np.full(4096, 524287 - GQA_COST, np.int64)            # N = 4096 * 524287 = 2^31 - 4096
     N = 4096 * 524287
-    for n_pieces in (256, 65535, 65536):
-        total, used = host_lib.plan(lens, n_pieces, 64, GQA_COST)
+    for n_pieces, skew in ((256, 0), (65535, 0), (65536, 0), (256, 200), (65536, 32)):
+        total, used = host_lib.plan(lens, n_pieces, 64, GQA_COST, skew)
         assert total == N and used == n_pieces
-        bounds = host_lib.piece_bounds(lens, n_pieces, 64, GQA_COST).astype(np.int64)
+        bounds = host_lib.piece_bounds(lens, n_pieces, 64, GQA_COST, skew).astype(np.int64)
         assert bounds[0] == 0 and bounds[-1] == N
         sizes = np.diff(bounds)
-        assert np.all(sizes > 0) and np.all(np.abs(sizes - N / used) <= 16)
+        assert np.all(sizes > 0) and np.all(np.abs(sizes - N / used) <= 16 + N / used * skew / 1000.0)
         for x in (0, 1, N // 3, N - 1):
-            assert host_lib.piece_of(lens, n_pieces, 64, GQA_COST, x) == int(np.searchsorted(bounds, x, side="right")) - 1
+            assert host_lib.piece_of(lens, n_pieces, 64, GQA_COST, x, skew) == int(np.searchsorted(bounds, x, side="right")) - 1
     segs = host_lib.piece_segments(lens, 65536, 64, GQA_COST, 65535)
     assert segs[-1][0] == 4095 and segs[-1][2] == lens[-1]
     too_many = np.full(4096, 524288, np.int64)                   # N = 2^31 + ...: outside the limit
