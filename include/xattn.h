@@ -183,7 +183,7 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  *                               before each part is cut into equal pieces: 0 = the kernel's default,
  *                               n = 1..201: the even XCDs' parts are longer and the odd ones' shorter by
  *                               (n - 1) per mille (1 = equal parts).  Applies when the pieces in use are a
- *                               multiple of 8 and hold 64 positions or more; results do not depend on it.
+ *                               multiple of 8 and hold 512 positions or more; results do not depend on it.
  * Values outside [0, 65536] give XATTN_EINVAL.  Process-wide.
  */
 enum { XATTN_CFG_PIECES = 0, XATTN_CFG_MIN_PIECE_TOKENS = 1, XATTN_CFG_TIMING = 2, XATTN_CFG_PATH = 3,

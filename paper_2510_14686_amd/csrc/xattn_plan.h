@@ -36,6 +36,7 @@ struct Plan {
     int xcd_skew;   // per mille; see piece_bound
 };
 constexpr int kMaxXcdSkew = 200;
+constexpr int kMinSkewPiece = 32 * kPlanRound;      // positions per piece from which the XCD skew applies
 
 XATTN_HD int clamp_len(int v) { return v > 0 ? v : 0; }
 // Stream positions of a sequence of `len` tokens (any sign).
@@ -48,8 +49,9 @@ XATTN_HD Plan plan_for_total(int total, int n_pieces, int min_piece, int seg_cos
     pl.total = total;
     pl.n_pieces = n < n_pieces ? n : n_pieces;
     pl.seg_cost = seg_cost;
-    // the skew needs the eight XCD parts to hold the same number of pieces, of a few blocks at least
-    const bool can_skew = xcd_skew > 0 && pl.n_pieces % 8 == 0 && total / pl.n_pieces >= 4 * kPlanRound;
+    // the skew needs the eight XCD parts to hold the same number of pieces, and pieces long enough for a
+    // few per cent of them to be a block or more
+    const bool can_skew = xcd_skew > 0 && pl.n_pieces % 8 == 0 && total / pl.n_pieces >= kMinSkewPiece;
     pl.xcd_skew = can_skew ? (xcd_skew < kMaxXcdSkew ? xcd_skew : kMaxXcdSkew) : 0;
     return pl;
 }
@@ -65,7 +67,10 @@ XATTN_HD uint32_t scaled_index(uint32_t i, uint32_t span, uint32_t m) { return i
 // N * (x + (x odd ? skew : 0)) / 8 (skew = xcd_skew / 1000: even parts are longer by that fraction, odd
 // parts shorter), and every part into n / 8 equal pieces.  xcd_skew = 0: eight equal parts.
 XATTN_HD uint32_t xcd_part_start(const Plan& pl, int x) {
-    return (uint32_t)(((uint64_t)(uint32_t)pl.total * (uint32_t)(1000 * x + ((x & 1) ? pl.xcd_skew : 0))) / 8000u);
+    // 32-bit arithmetic: N * x / 8 and N * skew / 8000, each as quotient part plus remainder part
+    const uint32_t t = (uint32_t)pl.total, ux = (uint32_t)x, sk = (uint32_t)pl.xcd_skew;
+    const uint32_t even = (t / 8u) * ux + (t % 8u) * ux / 8u;
+    return (x & 1) ? even + (t / 8000u) * sk + (t % 8000u) * sk / 8000u : even;
 }
 
 // Piece p owns stream positions [piece_bound(p), piece_bound(p + 1)): floor(p * N / n_pieces) (or its

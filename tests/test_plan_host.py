@@ -129,7 +129,7 @@ def test_unequal_xcd_parts(name, lens, n_pieces, min_piece, skew):
     if N == 0:
         return
     assert np.all(sizes > 0) and np.all(bounds[:-1] % 16 == 0)
-    skewed = used % 8 == 0 and N // used >= 64
+    skewed = used % 8 == 0 and N // used >= 512
     if skewed:
         m = used // 8
         for x in range(8):
