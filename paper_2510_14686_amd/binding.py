@@ -97,6 +97,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         if p != _build.LIB_PATH:
             raise FileNotFoundError(p)
         p = _build.build()
+    elif p == _build.LIB_PATH and _build.is_stale():
+        # a built library is loaded as it is (builds happen in build(), not here); say so when it is old
+        import warnings
+        warnings.warn("libxattn.so is older than its sources; run paper_2510_14686_amd/build.py to rebuild it")
     lib = bind(ctypes.CDLL(p))
     if path is None:
         _lib = lib

@@ -44,6 +44,11 @@ def _stale(lib: str) -> bool:
     return any(os.path.getmtime(f) > t for f in _dependencies())
 
 
+def is_stale(lib: str = LIB_PATH) -> bool:
+    """True when the built library is missing or older than any source or header it is built from."""
+    return _stale(lib)
+
+
 def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
