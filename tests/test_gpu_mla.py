@@ -166,3 +166,30 @@ def test_mla_scaled_down_workloads(name):
     out_bits, lse = gpu_mla(q, cs, lens, w.scale, xtensor=True, seed=w.seed)
     ref_out, ref_lse = oracle.mla(q, cs, lens, w.d_latent, w.scale)
     assert_parity(out_bits, lse, ref_out, ref_lse, w.name)
+
+
+def test_mla_few_dominant_keys_need_the_exact_weights():
+    """Rows that a few keys carry: 16 query tokens on a 16-token sequence (token t sees t + 1 keys) and a
+    peaked softmax on longer ones.  Their outputs reach |o| in [2, 4), where rounding the result to bf16
+    alone takes up to 7.8e-3 of the 1e-2 bar, so the weights must go into the value product with more
+    than 8 bits: the default does that for the first 128 keys of a segment and wherever a key carries a
+    quarter of its row.  With one bf16 per weight everywhere (XATTN_CFG_PV_MODE = 2) the same input is
+    measurably further from the oracle on exactly those rows."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity, errors
+    T, H = 16, 64
+    lens = [16, 17, 40, 777, 3000]
+    B = len(lens)
+    q, cs = _case(260, lens, T, H)
+    q = f32_to_bf16(bf16_to_f32(q) * np.float32(3.0))                 # peaked: a few keys per row
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE)
+    assert np.max(np.abs(ref_out)) > 3.0                               # the case does reach large outputs
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla dominant keys, default weights")
+    e_default = errors(out_bits, lse, ref_out, ref_lse)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, 2)
+    out2, lse2 = gpu_mla(q, cs, lens, SCALE)
+    e_single = errors(out2, lse2, ref_out, ref_lse)
+    print("max_abs / row rel-L2: default %.2e / %.2e, one bf16 per weight %.2e / %.2e"
+          % (e_default[0], e_default[1], e_single[0], e_single[1]), flush=True)
+    assert e_default[1] < e_single[1]                                  # the row error shows the weights' precision
