@@ -13,8 +13,9 @@
 // 128 registers) stay resident for the whole piece.  Of the tile's Q, 13 of the 18 MFMA steps stay in
 // registers (52); each lane parks its chunks of the other 5 in LDS and reads them back per block,
 // which leaves the registers for fetching operands ahead of the MFMAs.  (Workgroups of four waves,
-// one per SIMD with 512 registers and two tiles each, read every LDS operand half as often, but the
-// compiler keeps all MFMA results in the 256 accumulation registers and that layout needs 272.)
+// one per SIMD with 512 registers and two tiles each, read every LDS operand half as often: built
+// below as mla_block_pp and selectable, but a lone wave per SIMD has nobody to cover its softmax and
+// its longer prologue and epilogue, and it measures about 10 % slower.)
 // All waves share each 32-key block of the cache through LDS:
 //   * the block (32 x 1152 bytes, contiguous in memory) goes from HBM straight into LDS (buffer loads
 //     with the LDS destination, 1 KiB per wave instruction, no staging registers), once per
@@ -88,6 +89,10 @@ constexpr int kLoAlways = 1;                     // hi + lo bf16 parts everywher
 constexpr int kLoDynamic = 2;                    // hi + lo parts only in blocks with a dominant key
 constexpr int kExactBlocks = 4;                  // default mode: the first blocks of a segment run as kLoAlways
 constexpr float kDominantShare = 4.0f;           // a key is dominant from 1 / 4 of the row's running sum
+// Eight waves: the first wave of each SIMD issues its loads of the block after next behind the block's
+// arithmetic, the second one ahead of it, so the two run a fraction of a phase apart and one's vector
+// work falls on the other's MFMAs more often (measured: 3-4 % of the kernel).
+constexpr bool kSkewWaves = true;
 constexpr int kStages = 3;                       // LDS block buffers: two blocks in flight behind the one in use
 
 typedef short s16x4v_t __attribute__((ext_vector_type(4)));
@@ -143,21 +148,59 @@ __device__ __forceinline__ DmaLane dma_lane(int lane) {
     d.tail_row = (c < 8 && i < kTailRowsPerLoad) ? i : 64;
     return d;
 }
+// Load q (of this wave's (kDmaPerBlock + NW - 1) / NW) of a block.
+template <int NW>
+__device__ __forceinline__ void block_load(char* lds_block, u32x4_t rc, int j_block, int wave, const DmaLane& dma, int q) {
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
+    const int g = wave + q * NW;             // wave-uniform
+    if (g < kMlaKeys) {
+        dma16(rc, lds0 + g * kPitch, dma.main_off, (uint32_t)(j_block + g) * kRowB);
+    } else if (g < kDmaPerBlock) {
+        const int p = g - kMlaKeys;
+        if (p * kTailRowsPerLoad + dma.tail_row < kMlaKeys)
+            dma16(rc, lds0 + kTailOff + p * (kTailRowsPerLoad * kTailPitch), dma.tail_off,
+                  (uint32_t)(j_block + p * kTailRowsPerLoad) * kRowB);
+    }
+}
+// The same for workgroups of four waves, as few scalar instructions as possible (the caller places
+// them between MFMAs): which loads fill the tail area is then known from q alone, and the tail loads
+// run with all lanes.  The lanes that "fetch nothing" above then fetch bytes that do no harm: chunks
+// 72 and 73 of a row (the start of the next row) land in the padding of the tail pitch, lanes 60-63
+// fetch what the next tail load puts in the same place, and rows past the block land behind the tail
+// area, inside the buffer (kLdsBlock counts the last load in full).  Bytes past the sequence read as zero.
+struct Dma4 {
+    uint32_t lds_main, lds_tail;       // LDS address of this wave's first main / tail load
+    uint32_t mem_main, mem_tail;       // byte offsets of the same in the sequence's cache
+    uint32_t tail_off;                 // per lane: (lane / 10) rows + chunk 64 + lane % 10
+};
+__device__ __forceinline__ Dma4 dma4_for(char* lds_block, int j_block, int wave, int lane) {
+    Dma4 d;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
+    d.lds_main = lds0 + wave * kPitch;
+    d.lds_tail = lds0 + kTailOff + wave * (kTailRowsPerLoad * kTailPitch);
+    d.mem_main = (uint32_t)(j_block + wave) * kRowB;
+    d.mem_tail = (uint32_t)(j_block + wave * kTailRowsPerLoad) * kRowB;
+    d.tail_off = (uint32_t)((lane / 10) * kRowB + 1024 + (lane % 10) * 16);
+    return d;
+}
+template <int Q>
+__device__ __forceinline__ void block_load4(const Dma4& d, u32x4_t rc, uint32_t main_off, int wave) {
+    constexpr int kMainLoads = kMlaKeys / 4;         // loads 0..7 of a wave are rows wave + 4 q
+    if constexpr (Q < kMainLoads) {
+        dma16(rc, d.lds_main + Q * 4 * kPitch, main_off, d.mem_main + Q * 4 * kRowB);
+    } else if constexpr (4 * (Q - kMainLoads) + 3 < kTailLoads) {      // tail loads wave + 4 (Q - 8), all four waves
+        dma16(rc, d.lds_tail + (Q - kMainLoads) * 4 * (kTailRowsPerLoad * kTailPitch), d.tail_off,
+              d.mem_tail + (Q - kMainLoads) * 4 * kTailRowsPerLoad * kRowB);
+    } else if constexpr (4 * (Q - kMainLoads) < kTailLoads) {          // the last ones: the first waves only
+        if (wave + 4 * (Q - kMainLoads) < kTailLoads)
+            dma16(rc, d.lds_tail + (Q - kMainLoads) * 4 * (kTailRowsPerLoad * kTailPitch), d.tail_off,
+                  d.mem_tail + (Q - kMainLoads) * 4 * kTailRowsPerLoad * kRowB);
+    }
+}
 template <int NW>
 __device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_block, int wave, const DmaLane& dma) {
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
 #pragma unroll
-    for (int q = 0; q < (kDmaPerBlock + NW - 1) / NW; ++q) {
-        const int g = wave + q * NW;             // wave-uniform
-        if (g < kMlaKeys) {
-            dma16(rc, lds0 + g * kPitch, dma.main_off, (uint32_t)(j_block + g) * kRowB);
-        } else if (g < kDmaPerBlock) {
-            const int p = g - kMlaKeys;
-            if (p * kTailRowsPerLoad + dma.tail_row < kMlaKeys)
-                dma16(rc, lds0 + kTailOff + p * (kTailRowsPerLoad * kTailPitch), dma.tail_off,
-                      (uint32_t)(j_block + p * kTailRowsPerLoad) * kRowB);
-        }
-    }
+    for (int q = 0; q < (kDmaPerBlock + NW - 1) / NW; ++q) block_load<NW>(lds_block, rc, j_block, wave, dma, q);
 }
 
 // max / sum over the four lanes (kb = 0..3) that hold the same row: lane-swap instructions, no LDS.
@@ -200,6 +243,12 @@ typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
     const f32x2_t v = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
+}
+
+// Two values rounded to bf16 (nearest even) and packed: the conversion instruction.
+__device__ __forceinline__ uint32_t cvt_bf16(float a, float b) {
+    const f32x2_t v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Scheduling groups (the group sizes must be compile-time constants, hence the templates).
@@ -393,6 +442,266 @@ __device__ __forceinline__ void mla_block(MlaTile (&st)[RT], const char* qk_base
     }
 }
 
+// ----------------------------------------------------------------------- two row tiles per wave
+// One wave per SIMD with 512 registers: the output accumulators of two 16-row tiles (256) in the
+// accumulation registers, everything else in the ordinary ones.  Every operand fragment read from LDS
+// feeds the MFMAs of both tiles where the order of the work allows it: with one tile per wave each
+// MFMA needs a fragment of its own, 1 KiB per 16 cycles and SIMD, which is all the LDS delivers.
+// A block runs as scores of both tiles (every key fragment feeds two MFMAs), the two softmaxes slice
+// by slice in turn (two independent chains of dependent instructions), values of both tiles (every
+// value fragment feeds two MFMAs).
+// The MFMAs are assembly statements: their accumulators can then be named (scores in ordinary
+// registers, outputs in accumulation registers; through the builtin the compiler puts every MFMA
+// result into the accumulation registers, which the outputs fill alone), and such statements keep
+// their order among themselves and against memory operations, so LDS reads stay where they are
+// written, a fixed number of MFMAs ahead of their use.  Vector instructions do move across them;
+// the softmax is therefore cut into slices of a few instructions whose results pass through an empty
+// statement of the same kind (pin): a slice cannot start before the pin its inputs came through nor
+// end after its own.
+//
+// What the compiler cannot see of an MFMA inside a statement: a vector instruction may read a result
+// register only once the MFMA has left the pipe, so a few idle cycles (mfma_drain) stand between the
+// last score MFMA and the softmax, and between the last value MFMA of a segment and the epilogue; a
+// rescaling reads accumulators a phase or more after the MFMA that wrote them.
+constexpr int kFrags = 2 * kQSteps;              // key fragments per block, ordered (step, key tile)
+constexpr int kPpKAhead = 6;                     // key fragments in flight ahead of their MFMAs
+constexpr int kPpVAhead = 6;                     // value fragments (two reads each) in flight ahead of theirs
+constexpr int kPpDmaEvery = 3;                   // key fragments between two loads of the block after next
+constexpr int kSoftSlices = 27;
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>()), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) { static_for(f, std::make_integer_sequence<int, N>()); }
+
+__device__ __forceinline__ void mfma_first_v(f32x4_t& acc, bf16x8_t a, bf16x8_t b) {      // acc = a b
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_v(f32x4_t& acc, bf16x8_t a, bf16x8_t b) {            // acc += a b
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma_a(f32x4_t& acc, bf16x8_t a, bf16x8_t b) {            // the same on accumulation registers
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// Between the last MFMA statements and the first vector instructions that read their results: the 16
+// cycles an MFMA spends in the pipe and the write-back behind them, with a margin.  The results pass
+// through the statement, so their readers stay behind it.
+__device__ __forceinline__ void mfma_drain(f32x4_t& a, f32x4_t& b, f32x4_t& c, f32x4_t& d) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+__device__ __forceinline__ void mfma_drain_acc(f32x4_t& a, f32x4_t& b, f32x4_t& c, f32x4_t& d) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(a), "+a"(b), "+a"(c), "+a"(d));
+}
+template <typename A> __device__ __forceinline__ void pin(A& a) { asm volatile("" : "+v"(a)); }
+template <typename A, typename B> __device__ __forceinline__ void pin(A& a, B& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+template <typename A, typename B, typename C> __device__ __forceinline__ void pin(A& a, B& b, C& c) {
+    asm volatile("" : "+v"(a), "+v"(b), "+v"(c));
+}
+// max(a, b) of two scores (finite or -inf, no NaNs) as one instruction, the median of (a, b, largest
+// finite float): fmaxf() first quiets each operand it cannot prove to be the result of arithmetic
+// (matrix results, swapped lanes), an instruction apiece.
+__device__ __forceinline__ float max_num(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, 0x1.fffffep+127f); }
+
+// o *= alpha for a tile whose accumulators live in the accumulation registers: each passes through
+// ordinary registers, one after the other (the pins keep the compiler from fetching all 128 first,
+// which would evict everything else that lives in ordinary registers).
+__device__ __forceinline__ void rescale_acc(MlaTile& st, float alpha) {
+#pragma unroll
+    for (int ct = 0; ct < kColTiles; ++ct) {
+        if (ct > 0) asm volatile("" : "+a"(st.o[ct]), "+a"(st.o[ct - 1]));
+        st.o[ct] *= alpha;
+    }
+}
+
+// The softmax of one row tile over one block, between slices.
+struct SoftRow {
+    float p[8];                      // scores, then weights: keys 16 kt + 4 kb + i at index 4 kt + i
+    float t0, t1, t2, t3, sw0, sw1;
+    float mx, m_new, m_use, alpha, sum, sum_q, dom;
+    uint32_t h[4], lo[4];            // the weights as bf16 pairs, and what the rounding left
+    bool with_lo;
+};
+// Slice K of kSoftSlices.  s: the tile's scores (per key tile); st: its running state.
+template <int K, int kLo, bool kMasked, bool kPinned>
+__device__ __forceinline__ void soft_slice(SoftRow& r, MlaTile& st, const f32x4_t (&s)[2], float scale_log2, int j_block,
+                                           int lim, int kb) {
+    if constexpr (K == 0) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) r.p[t] = s[t >> 2][t & 3];
+        if (kMasked) {               // keys at or past lim (end of the segment, causal limit of the row) count as -inf
+#pragma unroll
+            for (int t = 0; t < 8; ++t) r.p[t] = (j_block + 16 * (t >> 2) + 4 * kb + (t & 3) < lim) ? r.p[t] : kNegInf;
+        }
+        r.t0 = max_num(r.p[0], r.p[1]);
+        r.t1 = max_num(r.p[2], r.p[3]);
+        if (kPinned) pin(r.t0, r.t1);
+    } else if constexpr (K == 1) {
+        r.t2 = max_num(r.p[4], r.p[5]);
+        r.t3 = max_num(r.p[6], r.p[7]);
+        if (kPinned) pin(r.t2, r.t3);
+    } else if constexpr (K == 2) {
+        r.t0 = max_num(r.t0, r.t1);
+        r.t2 = max_num(r.t2, r.t3);
+        if (kPinned) pin(r.t0, r.t2);
+    } else if constexpr (K == 3) {
+        swap16(max_num(r.t0, r.t2), r.sw0, r.sw1);
+        if (kPinned) pin(r.sw0, r.sw1);
+    } else if constexpr (K == 4) {
+        swap32(max_num(r.sw0, r.sw1), r.sw0, r.sw1);
+        if (kPinned) pin(r.sw0, r.sw1);
+    } else if constexpr (K == 5) {   // the reference maximum follows lazily, see mla_block
+        r.mx = max_num(r.sw0, r.sw1) * scale_log2;
+        r.m_new = r.mx > st.m + kLazyLog2 ? r.mx : st.m;
+        if (kPinned) pin(r.mx, r.m_new);
+    } else if constexpr (K == 6) {
+        r.m_use = (r.m_new == kNegInf) ? 0.0f : r.m_new;
+        r.alpha = fast_exp2(st.m - r.m_use);
+        if (kPinned) pin(r.m_use, r.alpha);
+    } else if constexpr (K >= 7 && K <= 14) {
+        r.p[K - 7] = fast_exp2(__builtin_fmaf(r.p[K - 7], scale_log2, -r.m_use));
+        if (kPinned) pin(r.p[K - 7], r.m_use);
+    } else if constexpr (K == 15) {
+        r.t0 = r.p[0] + r.p[1];
+        r.t1 = r.p[2] + r.p[3];
+        if (kPinned) pin(r.t0, r.t1);
+    } else if constexpr (K == 16) {
+        r.t2 = r.p[4] + r.p[5];
+        r.t3 = r.p[6] + r.p[7];
+        if (kPinned) pin(r.t2, r.t3);
+    } else if constexpr (K == 17) {
+        r.sum = (r.t0 + r.t1) + (r.t2 + r.t3);
+        swap16(r.sum, r.sw0, r.sw1);
+        if (kPinned) pin(r.sum, r.sw0, r.sw1);
+    } else if constexpr (K == 18) {
+        swap32(r.sw0 + r.sw1, r.sw0, r.sw1);
+        if (kPinned) pin(r.sw0, r.sw1);
+    } else if constexpr (K == 19) {
+        st.l = st.l * r.alpha + (r.sw0 + r.sw1);
+        st.m = r.m_new;
+        if (kPinned) pin(st.l, st.m);
+    } else if constexpr (K == 20) {  // a key with at least 1 / kDominantShare of the row's sum so far
+        if (kLo == kLoDynamic) {
+            r.dom = fast_exp2(r.mx - r.m_use) * kDominantShare >= st.l ? 1.0f : 0.0f;
+            if (kPinned) pin(r.dom);
+        }
+    } else if constexpr (K == 21 || K == 22) {
+#pragma unroll
+        for (int u = 2 * (K - 21); u < 2 * (K - 21) + 2; ++u) {
+            const f32x2_t pp = {r.p[2 * u], r.p[2 * u + 1]};
+            r.h[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp, bf16x2_t));
+        }
+        if (kPinned) pin(r.h[2 * (K - 21)], r.h[2 * (K - 21) + 1]);
+    } else if constexpr (K == 23) {  // the sum of the rounded weights: each pair times (1, 1), added in fp32
+        r.sum_q = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) r.sum_q = dot2_bf16(r.h[u], 0x3f803f80u, r.sum_q);
+        if (kPinned) pin(r.sum_q);
+    } else if constexpr (K == 24 || K == 25) {
+        if (kLo != kLoNever) {
+#pragma unroll
+            for (int u = 2 * (K - 24); u < 2 * (K - 24) + 2; ++u) {
+                const f32x2_t pp = {r.p[2 * u], r.p[2 * u + 1]};
+                const f32x2_t back = __builtin_convertvector(__builtin_bit_cast(bf16x2_t, r.h[u]), f32x2_t);
+                r.lo[u] = __builtin_bit_cast(uint32_t, __builtin_convertvector(pp - back, bf16x2_t));
+            }
+            if (kPinned) pin(r.lo[2 * (K - 24)], r.lo[2 * (K - 24) + 1]);
+        }
+    } else if constexpr (K == 26) {
+        r.with_lo = kLo == kLoAlways || (kLo == kLoDynamic && __builtin_amdgcn_ballot_w64(r.dom != 0.0f) != 0);
+        st.lq = st.lq * r.alpha + (r.with_lo ? r.sum : r.sum_q);
+        if (kPinned) pin(st.lq);
+    }
+}
+
+// issue(q): the caller's load q of the block after next (a wave-wide load into LDS); they are spread
+// over the score phase, one every kPpDmaEvery fragments: issued together behind the barrier they queue
+// up in front of the memory pipeline and hold every wave until the last one is accepted.
+template <int kLo, bool kMasked, typename Issue>
+__device__ __forceinline__ void mla_block_pp(MlaTile (&st)[2], const char* qk_base, const char* qt_base, const char* pv_base,
+                                             const bf16x8_t (&qop)[2][kQRegSteps], const char* q_lds, float scale_log2,
+                                             int j_block, const int (&lim)[2], int kb, Issue issue) {
+    f32x4_t s[2][2];                 // [row tile][key tile]
+    bf16x8_t ka[kFrags], ql[2][kQSteps - kQRegSteps], va[kColTiles];
+    SoftRow sr[2];
+    // Key fragment F = (step, key tile); with key tile 0 of a step from kQRegSteps on come the lane's
+    // parked chunks of Q for both row tiles.
+    auto load_k = [&](auto f_c) {
+        constexpr int F = decltype(f_c)::value, step = F >> 1, kt = F & 1;
+        if constexpr (step < kMainSteps) ka[F] = *reinterpret_cast<const bf16x8_t*>(qk_base + kt * kTileB + step * 64);
+        else ka[F] = *reinterpret_cast<const bf16x8_t*>(qt_base + kt * kTailTileB + (step - kMainSteps) * 64);
+        if constexpr (kt == 0 && step >= kQRegSteps) {
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+                ql[rt][step - kQRegSteps] =
+                    *reinterpret_cast<const bf16x8_t*>(q_lds + rt * kQLdsWave + (step - kQRegSteps) * 1024);
+        }
+    };
+    // Value fragment of column tile ct: see mla_block for the layout.
+    auto read_v = [&](int ct) {
+        const s16x4v_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4v_t*)(pv_base + ct * 32));
+        const s16x4v_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4v_t*)(pv_base + kTileB + ct * 32));
+        const u32x2_t w0 = __builtin_bit_cast(u32x2_t, v0), w1 = __builtin_bit_cast(u32x2_t, v1);
+        return __builtin_bit_cast(bf16x8_t, u32x4_t{w0.x, w0.y, w1.x, w1.y});
+    };
+    auto load_v = [&](auto i_c) { va[decltype(i_c)::value] = read_v(decltype(i_c)::value); };
+
+    // Scores of both tiles: every key fragment feeds two MFMAs (four independent accumulators).
+    static_for<kPpKAhead>(load_k);
+    static_for<kFrags>([&](auto f_c) {
+        constexpr int F = decltype(f_c)::value, step = F >> 1, kt = F & 1;
+        if constexpr (F + kPpKAhead < kFrags) load_k(std::integral_constant<int, F + kPpKAhead>());
+        else if constexpr (F + kPpKAhead - kFrags < kPpVAhead) load_v(std::integral_constant<int, F + kPpKAhead - kFrags>());
+        if constexpr (F % kPpDmaEvery == kPpDmaEvery - 1) issue(std::integral_constant<int, F / kPpDmaEvery>());
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            bf16x8_t qv;
+            if constexpr (step < kQRegSteps) qv = qop[rt][step];
+            else qv = ql[rt][step - kQRegSteps];
+            if constexpr (step == 0) mfma_first_v(s[rt][kt], ka[F], qv);
+            else mfma_v(s[rt][kt], ka[F], qv);
+        }
+    });
+    static_assert(kPpVAhead <= kPpKAhead, "the first value fragments are fetched in the last score steps");
+    mfma_drain(s[0][0], s[0][1], s[1][0], s[1][1]);
+    // Softmax of both tiles, slice by slice in turn: two independent chains of dependent instructions.
+    static_for<kSoftSlices>([&](auto k_c) {
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+            soft_slice<decltype(k_c)::value, kLo, kMasked, false>(sr[rt], st[rt], s[rt], scale_log2, j_block, lim[rt], kb);
+    });
+    bf16x8_t ph[2], pl[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+        if (__builtin_amdgcn_ballot_w64(sr[rt].alpha != 1.0f) != 0) rescale_acc(st[rt], sr[rt].alpha);       // about once per segment
+        ph[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{sr[rt].h[0], sr[rt].h[1], sr[rt].h[2], sr[rt].h[3]});
+        if (kLo != kLoNever) pl[rt] = __builtin_bit_cast(bf16x8_t, u32x4_t{sr[rt].lo[0], sr[rt].lo[1], sr[rt].lo[2], sr[rt].lo[3]});
+    }
+    // Values of both tiles: every value fragment feeds two MFMAs (four with the lo parts).
+    static_for<kColTiles>([&](auto i_c) {
+        constexpr int I = decltype(i_c)::value;
+        if constexpr (I + kPpVAhead < kColTiles) load_v(std::integral_constant<int, I + kPpVAhead>());
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) mfma_a(st[rt].o[I], va[I], ph[rt]);
+        if (kLo == kLoAlways) {
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt) mfma_a(st[rt].o[I], va[I], pl[rt]);
+        }
+    });
+    if (kLo == kLoDynamic) {
+        // The rare block with a dominant key: a second pass over the value fragments with the lo parts.
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+            if (!sr[rt].with_lo) continue;
+#pragma unroll
+            for (int ct = 0; ct < kColTiles; ++ct) mfma_a(st[rt].o[ct], read_v(ct), pl[rt]);
+        }
+    }
+}
+
 // kMode: 0 = default (hi + lo weights in the first kExactBlocks blocks of a segment and wherever a key
 // dominates its row), 1 = hi + lo weights everywhere, 2 = one bf16 per weight everywhere.
 template <int NW, int RT, int kMode>
@@ -496,28 +805,66 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
         fence();                  // the Q chunks in LDS are read back by the lane that wrote them
 
         const int n_blocks = (j1 - j0 + kMlaKeys - 1) / kMlaKeys;
-        if (n_blocks > 1) block_to_lds<NW>(lds_c + kLdsBlock, rc, j0 + kMlaKeys, wave, dma);   // block 1 -> buffer 1
+        if constexpr (RT == 2) {
+            // block 1 -> buffer 1; with two tiles per wave every block has its loads, past the segment's
+            // end against an empty buffer (see the block loop), so that the waits need no case.
+            u32x4_t rc1 = rc;
+            if (n_blocks <= 1) rc1[2] = 0u;
+            block_to_lds<NW>(lds_c + kLdsBlock, rc1, j0 + kMlaKeys, wave, dma);
+        } else {
+            if (n_blocks > 1) block_to_lds<NW>(lds_c + kLdsBlock, rc, j0 + kMlaKeys, wave, dma);   // block 1 -> buffer 1
+        }
         int cur_buf = 0, next_buf = 2;         // block blk sits in buffer blk % 3, block blk + 2 goes to next_buf
         // One block: every wave waits for its own loads of block blk (those of block blk + 1 may stay
         // in flight), then the barrier: block blk is in LDS and everyone is done reading block
         // blk - 1, whose buffer the loads of block blk + 2 may overwrite.
-        auto step = [&](int blk, auto lo_mode) {
+        auto step = [&](int blk, auto lo_mode, auto masked) {
             const char* cur = lds_c + cur_buf * kLdsBlock;
-            dma_wait(blk + 1 < n_blocks ? my_loads : 0);
+            dma_wait(RT == 2 || blk + 1 < n_blocks ? my_loads : 0);
             __syncthreads();
-            if (blk + 2 < n_blocks)
-                block_to_lds<NW>(lds_c + next_buf * kLdsBlock, rc, j0 + (blk + 2) * kMlaKeys, wave, dma);
-            mla_block<RT, decltype(lo_mode)::value>(st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2,
-                                                    j0 + blk * kMlaKeys, lim, kb);
+            if constexpr (RT == 2) {
+                static_assert(RT != 2 || (kDmaPerBlock + NW - 1) / NW <= kFrags / kPpDmaEvery, "a slot for every load");
+                // The loads of block blk + 2, spread over the score phase.  Past the segment's end they
+                // run against an empty buffer (nothing is fetched, zeros land in the free LDS buffer),
+                // so that every block issues the same number of loads and the slots need no branch.
+                u32x4_t rc_next = rc;
+                if (blk + 2 >= n_blocks) rc_next[2] = 0u;
+                const Dma4 d4 = dma4_for(lds_c + next_buf * kLdsBlock, j0 + (blk + 2) * kMlaKeys, wave, lane);
+                mla_block_pp<decltype(lo_mode)::value, decltype(masked)::value>(
+                    st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb,
+                    [&](auto q_c) { block_load4<decltype(q_c)::value>(d4, rc_next, dma.main_off, wave); });
+            } else {
+                const bool late = kSkewWaves && NW == 8 && wave < 4;
+                if (blk + 2 < n_blocks && !late)
+                    block_to_lds<NW>(lds_c + next_buf * kLdsBlock, rc, j0 + (blk + 2) * kMlaKeys, wave, dma);
+                mla_block<RT, decltype(lo_mode)::value>(st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2,
+                                                        j0 + blk * kMlaKeys, lim, kb);
+                if (blk + 2 < n_blocks && late)
+                    block_to_lds<NW>(lds_c + next_buf * kLdsBlock, rc, j0 + (blk + 2) * kMlaKeys, wave, dma);
+            }
             cur_buf = cur_buf == kStages - 1 ? 0 : cur_buf + 1;
             next_buf = next_buf == kStages - 1 ? 0 : next_buf + 1;
         };
         // Default mode: the first blocks of a segment with hi + lo weights, the others with hi + lo
         // only where a key dominates.
         const int n_exact = kMode == 1 ? n_blocks : kMode == 2 ? 0 : (n_blocks < kExactBlocks ? n_blocks : kExactBlocks);
+        // Two tiles per wave: blocks that end at or below every row's limit (the end of the segment, the
+        // causal limit of the wave's first row) run without masking, the few others in the masked form.
+        int first_masked = n_blocks;
+        if constexpr (RT == 2) {
+            const int causal_min = L - T + wave_row0 / H + 1;
+            const int clear = ((causal_min < j1 ? causal_min : j1) - j0) / kMlaKeys;
+            first_masked = clear < 0 ? 0 : (clear < n_blocks ? clear : n_blocks);
+        }
+        const int n_exact_clear = n_exact < first_masked ? n_exact : first_masked;
         int blk = 0;
-        for (; blk < n_exact; ++blk) step(blk, std::integral_constant<int, kLoAlways>());
-        for (; blk < n_blocks; ++blk) step(blk, std::integral_constant<int, kMode == 0 ? kLoDynamic : kLoNever>());
+        for (; blk < n_exact_clear; ++blk) step(blk, std::integral_constant<int, kLoAlways>(), std::false_type());
+        for (; blk < first_masked; ++blk)
+            step(blk, std::integral_constant<int, kMode == 0 ? kLoDynamic : (kMode == 1 ? kLoAlways : kLoNever)>(), std::false_type());
+        for (; blk < n_blocks; ++blk) step(blk, std::integral_constant<int, kMode == 2 ? kLoNever : kLoAlways>(), std::true_type());
+        if constexpr (RT == 2) dma_wait(0);      // the empty loads behind the last block: they write (zeros) to the buffers
+        if constexpr (RT == 2)        // the accumulators are read below; all but the last were written long ago
+            mfma_drain_acc(st[0].o[kColTiles - 2], st[0].o[kColTiles - 1], st[1].o[kColTiles - 2], st[1].o[kColTiles - 1]);
         __syncthreads();          // everyone is done with the block buffers: they stage the output now
 
 #pragma unroll
@@ -546,25 +893,31 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
             // Rounded to 16 bits (bf16 results, fp16 partial rows), half a row at a time through the
             // block buffers, which are free between the segment's last block and the next segment's
             // first: two rounds per tile, each store instruction writing two whole 512-byte half rows.
+            // The stores go through a buffer descriptor over the sequence's (or slot's) rows: 32-bit
+            // offsets, and rows past rows_total fall outside and are dropped, so the loop has no branch.
             uint16_t* dst = whole ? prm.out + (long)b * rows_total * kDv : prm.part_o + slot * rows_total * kDv;
+            const uint64_t daddr = (uint64_t)(uintptr_t)dst;
+            const __amdgpu_buffer_rsrc_t rd = make_rsrc(
+                reinterpret_cast<void*>(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(daddr >> 32)) << 32) |
+                                        (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)daddr)),
+                (uint32_t)rows_total * (kDv * 2));
+            const uint32_t lane_dst = (uint32_t)((tile_row0 + (lane >> 5)) * (kDv * 2) + (lane & 31) * 16);
+            const char* lane_stage = stage + (lane >> 5) * kStagePitch + (lane & 31) * 16;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
 #pragma unroll
                 for (int c = 0; c < kColTiles / 2; ++c) {
                     const f32x4_t o = st[rt].o[(kColTiles / 2) * h + c] * sc;
                     uint2 w;
-                    w.x = whole ? pack_bf16(o[0], o[1]) : pack_f16(o[0], o[1]);
-                    w.y = whole ? pack_bf16(o[2], o[3]) : pack_f16(o[2], o[3]);
+                    w.x = whole ? cvt_bf16(o[0], o[1]) : pack_f16(o[0], o[1]);
+                    w.y = whole ? cvt_bf16(o[2], o[3]) : pack_f16(o[2], o[3]);
                     *reinterpret_cast<uint2*>(stage + n * kStagePitch + (16 * c + 4 * kb) * 2) = w;
                 }
                 fence();
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {          // 2 rows x 256 columns per instruction
-                    const int rl = 2 * i + (lane >> 5), rr = tile_row0 + rl;
-                    if (rr < rows_total) {
-                        const uint4 w = *reinterpret_cast<const uint4*>(stage + rl * kStagePitch + (lane & 31) * 16);
-                        *reinterpret_cast<uint4*>(dst + (long)rr * kDv + h * (kDv / 2) + (lane & 31) * 8) = w;
-                    }
+                for (int i = 0; i < 8; ++i) {          // rows 2 i and 2 i + 1, 256 columns each, per instruction
+                    const u32x4_t w = *reinterpret_cast<const u32x4_t*>(lane_stage + 2 * i * kStagePitch);
+                    __builtin_amdgcn_raw_buffer_store_b128(w, rd, (int)(lane_dst + 2 * i * (kDv * 2) + h * kDv), 0, 0);
                 }
                 fence();
             }
@@ -658,7 +1011,7 @@ hipError_t launch_mla_cfg(const MlaParams& prm, dim3 grid, hipStream_t stream) {
 // Workgroup shape for rows_total = q_len * n_heads query rows per sequence: (waves, 16-row tiles per
 // wave).  Automatic: one tile per wave, 8 waves from 65 rows on (two waves per SIMD, 256 registers
 // each).  layout 1: at most 4 waves of one tile (64 rows per workgroup); layout 2: 4 waves of two
-// tiles from 65 rows on (one wave per SIMD; its accumulators do not fit the register file and spill).
+// tiles from 65 rows on (one wave per SIMD, 512 registers).
 void mla_block_shape(int rows_total, int layout, int* waves, int* tiles_per_wave) {
     const int tiles = (rows_total + 15) / 16;
     *tiles_per_wave = (tiles > 4 && layout == 2) ? 2 : 1;
