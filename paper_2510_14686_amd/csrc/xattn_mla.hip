@@ -104,6 +104,13 @@ struct MlaTile {
     float lq;                  // this lane's share of the sum over the weights as they entered the value product
 };
 
+template <typename F, int... I>
+__device__ __forceinline__ void static_for(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>()), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) { static_for(f, std::make_integer_sequence<int, N>()); }
+
 // The loads are written as assembly so that the compiler does not order them against LDS reads: it
 // cannot tell the two halves of the double buffer apart and would wait for every outstanding load
 // before each read.  dma_wait() before the workgroup barrier is what makes a block visible.
@@ -162,45 +169,49 @@ __device__ __forceinline__ void block_load(char* lds_block, u32x4_t rc, int j_bl
                   (uint32_t)(j_block + p * kTailRowsPerLoad) * kRowB);
     }
 }
-// The same for workgroups of four waves, as few scalar instructions as possible (the caller places
-// them between MFMAs): which loads fill the tail area is then known from q alone, and the tail loads
-// run with all lanes.  The lanes that "fetch nothing" above then fetch bytes that do no harm: chunks
-// 72 and 73 of a row (the start of the next row) land in the padding of the tail pitch, lanes 60-63
-// fetch what the next tail load puts in the same place, and rows past the block land behind the tail
-// area, inside the buffer (kLdsBlock counts the last load in full).  Bytes past the sequence read as zero.
-struct Dma4 {
+// The same for workgroups of four or eight waves with as few scalar instructions as possible: which
+// loads fill the tail area is then known from q alone, and the tail loads run with all lanes.  The
+// lanes that "fetch nothing" above then fetch bytes that do no harm: chunks 72 and 73 of a row (the
+// start of the next row) land in the padding of the tail pitch, lanes 60-63 fetch what the next tail
+// load puts in the same place, and rows past the block land behind the tail area, inside the buffer
+// (kLdsBlock counts the last load in full).  Bytes past the sequence read as zero.
+struct DmaWave {
     uint32_t lds_main, lds_tail;       // LDS address of this wave's first main / tail load
     uint32_t mem_main, mem_tail;       // byte offsets of the same in the sequence's cache
-    uint32_t tail_off;                 // per lane: (lane / 10) rows + chunk 64 + lane % 10
 };
-__device__ __forceinline__ Dma4 dma4_for(char* lds_block, int j_block, int wave, int lane) {
-    Dma4 d;
+__device__ __forceinline__ DmaWave dma_wave_for(char* lds_block, int j_block, int wave) {
+    DmaWave d;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds_block;
     d.lds_main = lds0 + wave * kPitch;
     d.lds_tail = lds0 + kTailOff + wave * (kTailRowsPerLoad * kTailPitch);
     d.mem_main = (uint32_t)(j_block + wave) * kRowB;
     d.mem_tail = (uint32_t)(j_block + wave * kTailRowsPerLoad) * kRowB;
-    d.tail_off = (uint32_t)((lane / 10) * kRowB + 1024 + (lane % 10) * 16);
     return d;
 }
-template <int Q>
-__device__ __forceinline__ void block_load4(const Dma4& d, u32x4_t rc, uint32_t main_off, int wave) {
-    constexpr int kMainLoads = kMlaKeys / 4;         // loads 0..7 of a wave are rows wave + 4 q
+template <int NW, int Q>
+__device__ __forceinline__ void block_load_static(const DmaWave& d, u32x4_t rc, const DmaLane& dma, int wave) {
+    static_assert(NW == 4 || NW == 8, "the main rows must divide among the waves");
+    constexpr int kMainLoads = kMlaKeys / NW;        // loads 0 .. kMainLoads - 1 of a wave are rows wave + NW q
     if constexpr (Q < kMainLoads) {
-        dma16(rc, d.lds_main + Q * 4 * kPitch, main_off, d.mem_main + Q * 4 * kRowB);
-    } else if constexpr (4 * (Q - kMainLoads) + 3 < kTailLoads) {      // tail loads wave + 4 (Q - 8), all four waves
-        dma16(rc, d.lds_tail + (Q - kMainLoads) * 4 * (kTailRowsPerLoad * kTailPitch), d.tail_off,
-              d.mem_tail + (Q - kMainLoads) * 4 * kTailRowsPerLoad * kRowB);
-    } else if constexpr (4 * (Q - kMainLoads) < kTailLoads) {          // the last ones: the first waves only
-        if (wave + 4 * (Q - kMainLoads) < kTailLoads)
-            dma16(rc, d.lds_tail + (Q - kMainLoads) * 4 * (kTailRowsPerLoad * kTailPitch), d.tail_off,
-                  d.mem_tail + (Q - kMainLoads) * 4 * kTailRowsPerLoad * kRowB);
+        dma16(rc, d.lds_main + Q * NW * kPitch, dma.main_off, d.mem_main + Q * NW * kRowB);
+    } else if constexpr (NW * (Q - kMainLoads + 1) <= kTailLoads) {    // tail loads wave + NW (Q - kMainLoads), all waves
+        dma16(rc, d.lds_tail + (Q - kMainLoads) * NW * (kTailRowsPerLoad * kTailPitch), dma.tail_off,
+              d.mem_tail + (Q - kMainLoads) * NW * kTailRowsPerLoad * kRowB);
+    } else if constexpr (NW * (Q - kMainLoads) < kTailLoads) {         // the last ones: the first waves only
+        if (wave + NW * (Q - kMainLoads) < kTailLoads)
+            dma16(rc, d.lds_tail + (Q - kMainLoads) * NW * (kTailRowsPerLoad * kTailPitch), dma.tail_off,
+                  d.mem_tail + (Q - kMainLoads) * NW * kTailRowsPerLoad * kRowB);
     }
 }
 template <int NW>
 __device__ __forceinline__ void block_to_lds(char* lds_block, u32x4_t rc, int j_block, int wave, const DmaLane& dma) {
+    if constexpr (NW == 4 || NW == 8) {
+        const DmaWave d = dma_wave_for(lds_block, j_block, wave);
+        static_for<(kDmaPerBlock + NW - 1) / NW>([&](auto q_c) { block_load_static<NW, decltype(q_c)::value>(d, rc, dma, wave); });
+    } else {
 #pragma unroll
-    for (int q = 0; q < (kDmaPerBlock + NW - 1) / NW; ++q) block_load<NW>(lds_block, rc, j_block, wave, dma, q);
+        for (int q = 0; q < (kDmaPerBlock + NW - 1) / NW; ++q) block_load<NW>(lds_block, rc, j_block, wave, dma, q);
+    }
 }
 
 // max / sum over the four lanes (kb = 0..3) that hold the same row: lane-swap instructions, no LDS.
@@ -468,13 +479,6 @@ constexpr int kPpKAhead = 6;                     // key fragments in flight ahea
 constexpr int kPpVAhead = 6;                     // value fragments (two reads each) in flight ahead of theirs
 constexpr int kPpDmaEvery = 3;                   // key fragments between two loads of the block after next
 constexpr int kSoftSlices = 27;
-
-template <typename F, int... I>
-__device__ __forceinline__ void static_for(F&& f, std::integer_sequence<int, I...>) {
-    (f(std::integral_constant<int, I>()), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f) { static_for(f, std::make_integer_sequence<int, N>()); }
 
 __device__ __forceinline__ void mfma_first_v(f32x4_t& acc, bf16x8_t a, bf16x8_t b) {      // acc = a b
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "v"(b));
@@ -829,10 +833,10 @@ __global__ __launch_bounds__(64 * NW) void mla_decode_kernel(MlaParams prm) {
                 // so that every block issues the same number of loads and the slots need no branch.
                 u32x4_t rc_next = rc;
                 if (blk + 2 >= n_blocks) rc_next[2] = 0u;
-                const Dma4 d4 = dma4_for(lds_c + next_buf * kLdsBlock, j0 + (blk + 2) * kMlaKeys, wave, lane);
+                const DmaWave d4 = dma_wave_for(lds_c + next_buf * kLdsBlock, j0 + (blk + 2) * kMlaKeys, wave);
                 mla_block_pp<decltype(lo_mode)::value, decltype(masked)::value>(
                     st, cur + qk_off, cur + qt_off, cur + pv_off, qop, q_lds, prm.scale_log2, j0 + blk * kMlaKeys, lim, kb,
-                    [&](auto q_c) { block_load4<decltype(q_c)::value>(d4, rc_next, dma.main_off, wave); });
+                    [&](auto q_c) { block_load_static<NW, decltype(q_c)::value>(d4, rc_next, dma, wave); });
             } else {
                 const bool late = kSkewWaves && NW == 8 && wave < 4;
                 if (blk + 2 < n_blocks && !late)
