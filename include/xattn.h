@@ -160,7 +160,9 @@ int xattn_set_workspace(void* dev_ptr, size_t bytes);
  * Tuning knobs of the partition (section 4.4.3 Layer 3), for sweeps and for tests that show the
  * result does not depend on the partition.  key:
  *   XATTN_CFG_PIECES            number of equal-token pieces the batch's keys are cut into
- *                               (= workgroups launched); 0 = automatic (the CU count)
+ *                               (= workgroups launched); 0 = automatic (the CU count; xattn_mla_decode,
+ *                               where a piece is worked on by one workgroup per 128 query rows of a
+ *                               sequence: the CU count divided by that number)
  *   XATTN_CFG_MIN_PIECE_TOKENS  lower bound on a piece's tokens; 0 = default (64); values below 16
  *                               count as 16
  *   XATTN_CFG_TIMING            1 = record per-kernel events (see xattn_timing_read); 0 = off

@@ -63,6 +63,20 @@ struct WorkspaceLayout {
     size_t meta_off, ml_off, o_off, total;
 };
 
+// Pieces of a latent-KV call: as many as give one workgroup per compute unit when a piece is worked
+// on by several workgroups (one per group of query rows; they sit side by side on one XCD and share
+// the piece's cache rows in its L2).  More pieces than that only add partial rows: measured with 256
+// query rows per sequence, 128 pieces against 256 take 8 % off the call and 20 % off the merge.
+int mla_pieces_for(int n_cu, int q_len, int n_heads) {
+    if (g_cfg_pieces > 0) return g_cfg_pieces;
+    int waves = 1, tiles = 1;
+    mla_block_shape(q_len * n_heads, g_cfg_mla_layout, &waves, &tiles);
+    const int rows_per_group = 16 * waves * tiles;
+    const int n_groups = (q_len * n_heads + rows_per_group - 1) / rows_per_group;
+    const int pieces = n_cu / n_groups / 8 * 8;
+    return pieces < 8 ? 8 : pieces;
+}
+
 WorkspaceLayout layout_for(int batch, int q_len, int n_q_heads, int n_pieces) {
     const size_t slots = (size_t)n_pieces + (size_t)batch;
     const size_t rows = (size_t)q_len * (size_t)n_q_heads;
@@ -290,10 +304,9 @@ size_t xattn_workspace_bytes(int batch, int q_len, int n_q_heads, int n_kv_heads
 
 size_t xattn_mla_workspace_bytes(int batch, int q_len, int n_heads, int d_latent, int d_rope) {
     if (check_mla_shape(batch, q_len, n_heads, d_latent, d_rope) != XATTN_OK) return 0;
-    int pieces = g_cfg_pieces > 0 ? g_cfg_pieces : 256;
     DeviceState* d = nullptr;
-    if (g_cfg_pieces == 0 && device_state(&d, nullptr) == XATTN_OK) pieces = pieces_for(d->n_cu);
-    return mla_layout_for(batch, q_len, n_heads, pieces).total;
+    const int n_cu = device_state(&d, nullptr) == XATTN_OK ? d->n_cu : 256;
+    return mla_layout_for(batch, q_len, n_heads, mla_pieces_for(n_cu, q_len, n_heads)).total;
 }
 
 int xattn_set_workspace(void* dev_ptr, size_t bytes) {
@@ -352,7 +365,7 @@ int xattn_mla_decode(const void* q, const void* const* c_ptrs, const int32_t* kv
     DeviceState* d = nullptr;
     st = device_state(&d, nullptr);
     if (st != XATTN_OK) return st;
-    const int n_pieces = pieces_for(d->n_cu);
+    const int n_pieces = mla_pieces_for(d->n_cu, q_len, n_heads);
     const MlaWorkspaceLayout w = mla_layout_for(batch, q_len, n_heads, n_pieces);
     char* ws = nullptr;
     st = acquire_workspace(d, w.total, static_cast<hipStream_t>(stream), "xattn_mla_decode", &ws);

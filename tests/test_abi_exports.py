@@ -79,9 +79,13 @@ def test_workspace_sizes_of_both_operators():
             B, T, Hq = 64, 2, 32
             slots, rows = P + B, T * Hq
             assert binding.xattn_workspace_bytes(B, T, Hq, 8, 128) == up(B * 8) + up(slots * rows * 8) + up(slots * rows * 512)
+            # latent-KV: one workgroup per 128 query rows of a sequence works on a piece, and the automatic
+            # count gives one workgroup per compute unit
             H = 128
-            rows = T * H
-            assert binding.xattn_mla_workspace_bytes(B, T, H, 512, 64) == up(B * 8) + up(slots * rows * 16) + up(slots * rows * 1024)
+            for Tm in (1, 2, 3):
+                rows = Tm * H
+                slots = (pieces or 256 // Tm // 8 * 8) + B
+                assert binding.xattn_mla_workspace_bytes(B, Tm, H, 512, 64) == up(B * 8) + up(slots * rows * 16) + up(slots * rows * 1024)
     finally:
         binding.xattn_configure(binding.XATTN_CFG_PIECES, 0)
     for bad in ((0, 1, 128, 512, 64), (1, 1, 128, 256, 64), (1, 16, 512, 512, 64), (5000, 1, 8, 512, 64)):
