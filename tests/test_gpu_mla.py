@@ -105,6 +105,30 @@ def test_mla_weight_precision_modes_and_workgroup_shapes(pv_mode, layout):
     assert_parity(out_bits, lse, ref_out, ref_lse, "mla pv_mode=%d layout=%d" % (pv_mode, layout))
 
 
+@pytest.mark.parametrize("T,H,pv_mode,pieces", [(1, 128, 0, 0), (2, 128, 0, 0), (3, 80, 0, 37), (2, 72, 1, 0), (1, 128, 2, 8),
+                                               (4, 40, 0, 1024)])
+def test_mla_two_tiles_per_wave(T, H, pv_mode, pieces):
+    """The workgroup shape of four waves with two 16-row tiles each (from 65 query rows per sequence
+    on): whole and partial row groups, causal limits inside and across 32-key blocks (the masked and
+    the unmasked form of its block), every weight mode, ragged lengths, several partitions."""
+    import paper_2510_14686_amd as xa
+    from gpu_util import assert_parity
+    lens = [T, T + 1, 31 + T, 32 + T, 33 + T, 64, 129, 200, 640, 1500, 2100]
+    q, cs = _case(270 + 10 * T + pv_mode, lens, T, H)
+    ref_out, ref_lse = oracle.mla(q, cs, lens, DV, SCALE)
+    # Rows of one to four keys put out single value elements: the seeds are chosen so that none reaches
+    # 4, from where on rounding the reference itself to bf16 is off by more than the bar (checked here).
+    ref = np.asarray(ref_out, dtype=np.float64)
+    assert np.abs(bf16_to_f32(f32_to_bf16(ref.astype(np.float32))) - ref).max() < 8e-3
+    xa.xattn_configure(xa.XATTN_CFG_MLA_LAYOUT, 2)
+    xa.xattn_configure(xa.XATTN_CFG_PV_MODE, pv_mode)
+    xa.xattn_configure(xa.XATTN_CFG_PIECES, pieces)
+    if pieces:
+        xa.xattn_configure(xa.XATTN_CFG_MIN_PIECE_TOKENS, 16)
+    out_bits, lse = gpu_mla(q, cs, lens, SCALE)
+    assert_parity(out_bits, lse, ref_out, ref_lse, "mla two tiles T=%d H=%d pv_mode=%d pieces=%d" % (T, H, pv_mode, pieces))
+
+
 @pytest.mark.parametrize("scale_up", [4.0, 16.0])
 def test_mla_peaked_softmax(scale_up):
     """Large scores: a few keys carry nearly all the weight, the case where rounding the weights to
